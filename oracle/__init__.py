@@ -1,0 +1,151 @@
+"""Loader for the CPU oracle (plain C, fp64) of the OIM + SPU path.
+
+TEST INFRASTRUCTURE ONLY: imported by ``tests/``, by ``__graft_entry__.smoke``
+and by the ``cpu_baseline`` leg of ``bench.py``.  The product package never
+imports this module and this module never imports the product package.
+
+The functions below only marshal numpy arrays into ``luvc_oracle.c``; every
+step of the method lives in the C file.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "luvc_oracle.c")
+_LIB = os.path.join(_HERE, "libluvc_oracle.so")
+
+ROUND_NONE, ROUND_F32, ROUND_BF16 = 0, 1, 2
+
+
+def build(force: bool = True) -> str:
+    """Compile the oracle with gcc (``-O2``, OpenMP over independent images/samples)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(
+            ["gcc", "-O2", "-fopenmp", "-std=c99", "-D_GNU_SOURCE", "-shared", "-fPIC", "-Wall",
+             "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        build(force=False)
+        L = ctypes.CDLL(_LIB)
+        c_dp = ctypes.POINTER(ctypes.c_double)
+        c_lp = ctypes.POINTER(ctypes.c_int64)
+        c_ip = ctypes.POINTER(ctypes.c_int32)
+        i = ctypes.c_int
+        L.oracle_oim_pass.argtypes = [c_dp, c_lp, i, i, i, i, i, i, i, i, c_dp, c_lp, c_ip, c_ip, c_dp]
+        L.oracle_oim_pass.restype = i
+        L.oracle_oim_merge.argtypes = [c_dp, c_lp, i, i, i, i, c_ip, c_ip, i, i, i, c_dp, c_lp, c_ip, c_ip, c_dp]
+        L.oracle_oim_merge.restype = i
+        L.oracle_spu_mask.argtypes = [i, i, i, i]
+        L.oracle_spu_mask.restype = ctypes.c_double
+        L.oracle_spu_score.argtypes = [c_dp, i, i, i, i, i, c_dp, c_dp, c_dp]
+        L.oracle_spu_score.restype = i
+        L.oracle_spu_prune.argtypes = [c_dp, c_dp, i, i, i, i, c_ip, c_dp, c_dp]
+        L.oracle_spu_prune.restype = i
+        L.oracle_keep_count.argtypes = [i, ctypes.c_double]
+        L.oracle_keep_count.restype = i
+        _lib = L
+    return _lib
+
+
+def _dp(a):
+    return None if a is None else a.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+
+
+def _lp(a):
+    return None if a is None else a.ctypes.data_as(ctypes.POINTER(ctypes.c_int64))
+
+
+def _ip(a):
+    return None if a is None else a.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+
+
+def _f64(a):
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+def out_shape(H, W, passes):
+    for axis, m in passes:
+        if axis == 1:
+            W -= m
+        else:
+            H -= m
+    return H, W
+
+
+def oim_merge(x, passes, sizes=None, R=1, round_mode=ROUND_NONE):
+    """x [B,H,W,D] (any float dtype, widened to fp64); passes = [(axis, m), ...].
+
+    Returns dict(x, sizes, merged_map, kept_map, margin).
+    """
+    x = _f64(x)
+    B, H, W, D = x.shape
+    Ho, Wo = out_shape(H, W, passes)
+    if Ho < 1 or Wo < 1:
+        raise ValueError("schedule removes every token of an axis")
+    s_in = None if sizes is None else np.ascontiguousarray(sizes, dtype=np.int64).reshape(B, H, W)
+    x_out = np.empty((B, Ho, Wo, D), np.float64)
+    s_out = np.empty((B, Ho, Wo), np.int64)
+    merged = np.empty((B, H * W), np.int32)
+    kept = np.empty((B, Ho * Wo), np.int32)
+    axes = np.array([p[0] for p in passes], np.int32)
+    ms = np.array([p[1] for p in passes], np.int32)
+    margin = ctypes.c_double(float("inf"))
+    rc = lib().oracle_oim_merge(_dp(x), _lp(s_in), B, H, W, D, _ip(axes), _ip(ms), len(passes), R, round_mode,
+                                _dp(x_out), _lp(s_out), _ip(merged), _ip(kept), ctypes.byref(margin))
+    if rc != 0:
+        raise ValueError("oracle_oim_merge rejected its arguments")
+    return dict(x=x_out, sizes=s_out, merged_map=merged, kept_map=kept, margin=margin.value)
+
+
+def spu_mask(N, sigma, use_hamming=True):
+    return np.array([lib().oracle_spu_mask(k, N, sigma, int(bool(use_hamming))) for k in range(N)])
+
+
+def spu_score(x, sigma, use_hamming=True, want_filtered=False):
+    """x [B,N,D] -> scores [B,N] fp64 (and the filtered signal when asked)."""
+    x = _f64(x)
+    B, N, D = x.shape
+    scores = np.empty((B, N), np.float64)
+    filt = np.empty((B, N, D), np.float64) if want_filtered else None
+    mi = ctypes.c_double(0.0)
+    rc = lib().oracle_spu_score(_dp(x), B, N, D, sigma, int(bool(use_hamming)), _dp(scores), _dp(filt),
+                                ctypes.byref(mi))
+    if rc != 0:
+        raise ValueError("oracle_spu_score rejected its arguments")
+    if want_filtered:
+        return scores, filt, mi.value
+    return scores
+
+
+def spu_prune(scores, n_keep, x=None):
+    """scores [B,N] -> kept_idx [B,n_keep] ascending (+ gathered rows of x, + margin)."""
+    scores = _f64(scores)
+    B, N = scores.shape
+    kept = np.empty((B, n_keep), np.int32)
+    xo = None
+    D = 1
+    if x is not None:
+        x = _f64(x)
+        D = x.shape[2]
+        xo = np.empty((B, n_keep, D), np.float64)
+    margin = ctypes.c_double(float("inf"))
+    rc = lib().oracle_spu_prune(_dp(scores), _dp(x), B, N, D, n_keep, _ip(kept), _dp(xo), ctypes.byref(margin))
+    if rc != 0:
+        raise ValueError("oracle_spu_prune rejected its arguments")
+    return dict(kept_idx=kept, x=xo, margin=margin.value)
+
+
+def keep_count(N, ratio):
+    return lib().oracle_keep_count(N, float(ratio))
