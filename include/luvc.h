@@ -1,0 +1,157 @@
+/*
+ * luvc.h - C ABI of the MI355X (gfx950) implementation of LUVC's training-free
+ * visual-token compression hot path:
+ *
+ *   OIM  Orthogonal Iterative Merger   (paper Section 3.2, Algorithm 1)
+ *   SPU  Spectrum Pruning Unit         (paper Section 3.3, Eq. 4-8, Algorithm 2)
+ *
+ * General conventions
+ *   - "device" pointers are HIP device memory of the GPU that is current on the
+ *     calling thread; "host" pointers are ordinary process memory.
+ *   - The caller owns every buffer.  The library allocates no device memory; all
+ *     scratch lives in the caller's `workspace` (sized by the *_workspace_bytes
+ *     query for the same arguments, 256-byte aligned).
+ *   - Inputs are never modified.  Input, output and workspace buffers must not
+ *     overlap.
+ *   - All work is enqueued asynchronously on `hip_stream` (a hipStream_t passed as
+ *     void*, NULL = the default stream).  No call synchronises with the host or
+ *     copies device data to the host.
+ *   - Arguments are validated on the host before anything is enqueued; a call that
+ *     returns a status other than LUVC_OK has enqueued nothing.  luvc_last_error()
+ *     then describes the problem.
+ *   - Tensors are dense, row-major, innermost dimension D contiguous.  Flat token
+ *     index inside one grid: p = h * W + w.
+ *   - Non-finite input values give unspecified output VALUES, but every access
+ *     stays in bounds and index outputs stay well formed.
+ */
+#ifndef LUVC_H
+#define LUVC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    LUVC_OK = 0,
+    LUVC_ERR_INVALID_ARG = 1,  /* NULL pointer, non-positive size, inconsistent schedule ...   */
+    LUVC_ERR_UNSUPPORTED = 2,  /* valid request outside what the kernels implement              */
+    LUVC_ERR_WORKSPACE = 3,    /* workspace missing, misaligned or smaller than the query says  */
+    LUVC_ERR_HIP = 4           /* a HIP launch failed; luvc_last_error() carries hipGetErrorString */
+} luvc_status;
+
+typedef enum {
+    LUVC_F32 = 0,   /* IEEE binary32                                    */
+    LUVC_BF16 = 1   /* bfloat16 (upper half of binary32), 2 bytes/value */
+} luvc_dtype;
+
+/* One merge pass of OIM (Section 3.2): along axis 1 every row of W tokens becomes W-m
+ * tokens ("row merge", H x W -> H x (W-m)); along axis 0 every column of H tokens becomes
+ * H-m ("column merge").  m = number of tokens merged per line, 0 <= m <= ceil(len/2) and
+ * len-m >= 1.  The paper's setting is m = 2 (appendix "Iterative Strategy and Pseudocode of
+ * OIM"); m = ceil(len/2) halves the axis. */
+typedef struct {
+    int32_t axis; /* 1 = along W, 0 = along H */
+    int32_t m;
+} luvc_oim_pass;
+
+/* Version / build information: static string, never NULL. */
+const char* luvc_version(void);
+
+/* Text of the last error raised on the calling thread ("" if none).  Static storage. */
+const char* luvc_last_error(void);
+
+/*
+ * Merge schedule for a target token count (Section 3.2 order: row merge first, then
+ * column merge, alternating as in Algorithm 1's consecutive layers).  Starting from H x W,
+ * passes alternate W, H, W, ...; a pass halves its axis (m = ceil(len/2)) while the halved
+ * grid still holds at least target_tokens tokens; otherwise it takes the one m that lands
+ * exactly on target_tokens, and the schedule ends.
+ *   passes      host, capacity max_passes
+ *   n_passes    host, receives the number of passes written
+ * Returns LUVC_OK, or LUVC_ERR_INVALID_ARG when the target cannot be hit exactly or
+ * max_passes is too small.
+ */
+luvc_status luvc_oim_plan(int H, int W, int64_t target_tokens,
+                          luvc_oim_pass* passes, int max_passes, int* n_passes);
+
+/* Bytes of workspace luvc_oim_merge needs for these arguments (0 on invalid arguments). */
+size_t luvc_oim_workspace_bytes(int B, int H, int W, int D, luvc_dtype dtype,
+                                const luvc_oim_pass* passes, int n_passes);
+
+/*
+ * OIM: iterative merging of similar, spatially adjacent tokens along alternating grid axes
+ * while keeping the 2-D layout (Section 3.2; size vector s of Algorithm 1).
+ *
+ * One pass, on every line independently: tokens at even positions are merge sources, tokens
+ * at odd positions destinations.  Each source picks the more similar (cosine of the features,
+ * norms clamped at 1e-12, evaluated in fp64; tie -> lower position) of its adjacent
+ * destinations; the m sources with the highest similarity (tie -> lower position) are folded
+ * into their pick by size-weighted mean, sizes add; survivors keep their order.  The output
+ * of a pass is rounded once to `dtype` before the next pass reads it.
+ *
+ *   x           device [B,H,W,D] dtype
+ *   sizes_in    device [B,H,W] int32 >= 1, or NULL (every token counts 1)
+ *   passes      host [n_passes], applied in order; n_passes >= 1
+ *   target_tokens  0 = no check; otherwise must equal H' * W' of the schedule
+ *   x_out       device [B,H',W',D] dtype
+ *   sizes_out   device [B,H',W'] int32
+ *   merged_map  device [B,H*W] int32: input flat index -> output flat slot, or NULL
+ *   kept_map    device [B,H'*W'] int32: output slot -> input flat index of the token that
+ *               anchors it (the destination of a merged group), or NULL
+ * Limits: B*H*W < 2^31, sizes sums < 2^31.
+ */
+luvc_status luvc_oim_merge(const void* x, const int32_t* sizes_in,
+                           int B, int H, int W, int D, luvc_dtype dtype,
+                           const luvc_oim_pass* passes, int n_passes, int64_t target_tokens,
+                           void* x_out, int32_t* sizes_out, int32_t* merged_map, int32_t* kept_map,
+                           void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Bytes of workspace luvc_spu_score needs (0 on invalid arguments). */
+size_t luvc_spu_workspace_bytes(int B, int N, int D, luvc_dtype dtype, int sigma);
+
+/*
+ * SPU score (Section 3.3): per sample and channel, DFT along the token index n (Eq. 4),
+ * multiplication by the low-pass mask M[k] (Eq. 5-6), inverse DFT with 1/N (Eq. 7), then the
+ * L2 norm over the D channels of each filtered token (Eq. 8).
+ *
+ * Mask: with the folded frequency f(k) = min(k, N-k), M[k] = w(f) for f <= sigma and 0 above;
+ * w(f) = 0.54 + 0.46 cos(2 pi f / (N-1)) (Hamming window centred on DC; w = 1 when N = 1) if
+ * use_hamming, else w = 1 (the "wo HW" ablation of the paper's core-component table).
+ *
+ *   x           device [B,N,*] dtype, token n of sample b starts at x + (b*N + n)*row_stride
+ *   row_stride  elements between consecutive tokens, >= D
+ *   sigma       cut-off, 0 <= sigma <= N/2
+ *   scores      device [B,N] fp32
+ * Arithmetic is fp32 (bf16 is a storage type only).
+ */
+luvc_status luvc_spu_score(const void* x, int B, int N, int D, int64_t row_stride, luvc_dtype dtype,
+                           int sigma, int use_hamming, float* scores,
+                           void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Number of tokens to keep for a keep ratio: floor(ratio*N + 0.5) clamped to [1, N]. */
+int luvc_keep_count(int N, double keep_ratio);
+
+/*
+ * SPU prune (Algorithm 2, last two steps): keep the n_keep tokens with the largest score
+ * (equal scores: the lower index wins) and return them in their original order, gathering
+ * the ORIGINAL (unfiltered) tokens.
+ *
+ *   x           device [B,N,*] dtype with row_stride as above; may be NULL iff x_out is NULL
+ *   scores      device [B,N] fp32
+ *   n_keep      1..N
+ *   kept_idx    device [B,n_keep] int32, strictly ascending within a sample
+ *   x_out       device [B,n_keep,D] dtype (dense), or NULL for indices only
+ * Needs no workspace today; the arguments are kept so callers are ready for one
+ * (pass NULL / 0).
+ */
+luvc_status luvc_spu_prune(const void* x, const float* scores, int B, int N, int D, int64_t row_stride,
+                           luvc_dtype dtype, int n_keep, int32_t* kept_idx, void* x_out,
+                           void* workspace, size_t workspace_bytes, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LUVC_H */

@@ -1,0 +1,191 @@
+"""ctypes binding over ``libluvc.so`` - same names as the C ABI in ``include/luvc.h``.
+
+Argument marshalling only: every step of OIM and SPU runs in the HIP kernels.  PyTorch is used
+for device memory (tensors own the buffers) and for the current stream handle.  There is no
+CPU fallback: if the library is missing or cannot be loaded, importing callers get an error.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Sequence, Tuple
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libluvc.so")
+
+LUVC_OK, LUVC_ERR_INVALID_ARG, LUVC_ERR_UNSUPPORTED, LUVC_ERR_WORKSPACE, LUVC_ERR_HIP = range(5)
+LUVC_F32, LUVC_BF16 = 0, 1
+
+EXPORTS = ("luvc_version", "luvc_last_error", "luvc_oim_plan", "luvc_oim_workspace_bytes", "luvc_oim_merge",
+           "luvc_spu_workspace_bytes", "luvc_spu_score", "luvc_keep_count", "luvc_spu_prune")
+
+
+class LuvcPass(ctypes.Structure):
+    _fields_ = [("axis", ctypes.c_int32), ("m", ctypes.c_int32)]
+
+
+class LuvcError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"libluvc status {status}: {text}")
+        self.status = status
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load libluvc.so (built beforehand by ``paper_2512_09010_amd.build``); raises if it is absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(f"{LIB_PATH} is not built; run `python -m paper_2512_09010_amd.build` "
+                                "(there is no fallback implementation)")
+    L = ctypes.CDLL(LIB_PATH)
+    i, i64, vp, sz = ctypes.c_int, ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t
+    pp = ctypes.POINTER(LuvcPass)
+    L.luvc_version.restype = ctypes.c_char_p
+    L.luvc_last_error.restype = ctypes.c_char_p
+    L.luvc_oim_plan.argtypes = [i, i, i64, pp, i, ctypes.POINTER(i)]
+    L.luvc_oim_plan.restype = i
+    L.luvc_oim_workspace_bytes.argtypes = [i, i, i, i, i, pp, i]
+    L.luvc_oim_workspace_bytes.restype = sz
+    L.luvc_oim_merge.argtypes = [vp, vp, i, i, i, i, i, pp, i, i64, vp, vp, vp, vp, vp, sz, vp]
+    L.luvc_oim_merge.restype = i
+    L.luvc_spu_workspace_bytes.argtypes = [i, i, i, i, i]
+    L.luvc_spu_workspace_bytes.restype = sz
+    L.luvc_spu_score.argtypes = [vp, i, i, i, i64, i, i, i, vp, vp, sz, vp]
+    L.luvc_spu_score.restype = i
+    L.luvc_keep_count.argtypes = [i, ctypes.c_double]
+    L.luvc_keep_count.restype = i
+    L.luvc_spu_prune.argtypes = [vp, vp, i, i, i, i64, i, i, vp, vp, vp, sz, vp]
+    L.luvc_spu_prune.restype = i
+    _lib = L
+    return L
+
+
+def last_error() -> str:
+    return lib().luvc_last_error().decode()
+
+
+def _check(status: int):
+    if status != LUVC_OK:
+        raise LuvcError(status, last_error())
+
+
+def _passes(passes: Sequence[Tuple[int, int]]):
+    arr = (LuvcPass * max(1, len(passes)))()
+    for k, (axis, m) in enumerate(passes):
+        arr[k].axis, arr[k].m = int(axis), int(m)
+    return arr
+
+
+def _dtype_code(t) -> int:
+    import torch
+    if t.dtype == torch.float32:
+        return LUVC_F32
+    if t.dtype == torch.bfloat16:
+        return LUVC_BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _stream(stream) -> int:
+    import torch
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return int(s.cuda_stream)
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else int(t.data_ptr())
+
+
+def luvc_version() -> str:
+    return lib().luvc_version().decode()
+
+
+def luvc_keep_count(N: int, keep_ratio: float) -> int:
+    return lib().luvc_keep_count(int(N), float(keep_ratio))
+
+
+def luvc_oim_plan(H: int, W: int, target_tokens: int, max_passes: int = 16) -> List[Tuple[int, int]]:
+    arr = (LuvcPass * max_passes)()
+    n = ctypes.c_int(0)
+    _check(lib().luvc_oim_plan(H, W, int(target_tokens), arr, max_passes, ctypes.byref(n)))
+    return [(arr[k].axis, arr[k].m) for k in range(n.value)]
+
+
+def luvc_oim_workspace_bytes(B, H, W, D, dtype_code, passes) -> int:
+    return lib().luvc_oim_workspace_bytes(B, H, W, D, dtype_code, _passes(passes), len(passes))
+
+
+def out_grid(H: int, W: int, passes) -> Tuple[int, int]:
+    for axis, m in passes:
+        if axis == 1:
+            W -= m
+        else:
+            H -= m
+    return H, W
+
+
+def luvc_oim_merge(x, passes, sizes=None, target_tokens: int = 0, want_maps: bool = True, workspace=None, stream=None,
+                   out=None):
+    """x: CUDA tensor [B,H,W,D] (fp32 or bf16, contiguous).  Returns dict(x, sizes, merged_map, kept_map)."""
+    import torch
+    assert x.is_cuda and x.is_contiguous() and x.dim() == 4
+    B, H, W, D = x.shape
+    code = _dtype_code(x)
+    parr = _passes(passes)
+    Ho, Wo = out_grid(H, W, passes)
+    need = lib().luvc_oim_workspace_bytes(B, H, W, D, code, parr, len(passes))
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=x.device)
+    if out is None:
+        out = dict(
+            x=torch.empty((B, max(Ho, 0), max(Wo, 0), D), dtype=x.dtype, device=x.device),
+            sizes=torch.empty((B, max(Ho, 0), max(Wo, 0)), dtype=torch.int32, device=x.device),
+            merged_map=torch.empty((B, H * W), dtype=torch.int32, device=x.device) if want_maps else None,
+            kept_map=torch.empty((B, max(Ho, 0) * max(Wo, 0)), dtype=torch.int32, device=x.device) if want_maps else None,
+        )
+    if sizes is not None:
+        assert sizes.is_cuda and sizes.dtype == torch.int32 and sizes.is_contiguous() and sizes.numel() == B * H * W
+    _check(lib().luvc_oim_merge(_ptr(x), _ptr(sizes), B, H, W, D, code, parr, len(passes), int(target_tokens),
+                                _ptr(out["x"]), _ptr(out["sizes"]), _ptr(out.get("merged_map")), _ptr(out.get("kept_map")),
+                                _ptr(workspace), workspace.numel(), _stream(stream)))
+    return out
+
+
+def luvc_spu_workspace_bytes(B, N, D, dtype_code, sigma) -> int:
+    return lib().luvc_spu_workspace_bytes(B, N, D, dtype_code, sigma)
+
+
+def luvc_spu_score(x, sigma: int, use_hamming: bool = True, workspace=None, stream=None, out=None):
+    """x: CUDA tensor [B,N,D] (last dim contiguous; token stride may exceed D).  Returns scores [B,N] fp32."""
+    import torch
+    assert x.is_cuda and x.dim() == 3 and x.stride(2) == 1 and x.stride(0) == x.shape[1] * x.stride(1)
+    B, N, D = x.shape
+    code = _dtype_code(x)
+    need = lib().luvc_spu_workspace_bytes(B, N, D, code, int(sigma))
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=x.device)
+    if out is None:
+        out = torch.empty((B, N), dtype=torch.float32, device=x.device)
+    _check(lib().luvc_spu_score(_ptr(x), B, N, D, x.stride(1), code, int(sigma), int(bool(use_hamming)), _ptr(out),
+                                _ptr(workspace), workspace.numel(), _stream(stream)))
+    return out
+
+
+def luvc_spu_prune(x, scores, n_keep: int, gather: bool = True, stream=None, out=None):
+    """Returns dict(kept_idx [B,n_keep] int32 ascending, x [B,n_keep,D] or None)."""
+    import torch
+    assert scores.is_cuda and scores.dtype == torch.float32 and scores.is_contiguous() and scores.dim() == 2
+    B, N = scores.shape
+    D, stride, code, xp = 1, 1, LUVC_F32, None
+    if x is not None:
+        assert x.is_cuda and x.dim() == 3 and x.stride(2) == 1 and x.shape[:2] == scores.shape
+        D, stride, code, xp = x.shape[2], x.stride(1), _dtype_code(x), _ptr(x)
+    if out is None:
+        out = dict(kept_idx=torch.empty((B, max(n_keep, 0)), dtype=torch.int32, device=scores.device),
+                   x=torch.empty((B, max(n_keep, 0), D), dtype=x.dtype, device=x.device) if (gather and x is not None) else None)
+    _check(lib().luvc_spu_prune(xp, _ptr(scores), B, N, D, stride, code, int(n_keep), _ptr(out["kept_idx"]),
+                                _ptr(out.get("x")), None, 0, _stream(stream)))
+    return out

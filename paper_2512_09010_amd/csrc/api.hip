@@ -1,0 +1,258 @@
+// C ABI of libluvc (declared in include/luvc.h): argument validation, workspace carving and
+// dispatch to the gfx950 kernels.  Every check happens before the first launch, so a failing
+// call enqueues nothing.
+#include <cstdarg>
+#include <cstdio>
+#include <cmath>
+
+#include "common.hpp"
+#include "oim.hpp"
+#include "spu.hpp"
+
+namespace luvc {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char* fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+luvc_status check_launch(const char* what)
+{
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        set_error("%s: %s", what, hipGetErrorString(e));
+        return LUVC_ERR_HIP;
+    }
+    return LUVC_OK;
+}
+
+static bool dtype_ok(luvc_dtype dt) { return dt == LUVC_F32 || dt == LUVC_BF16; }
+static size_t esize(luvc_dtype dt) { return dt == LUVC_F32 ? 4 : 2; }
+
+// Shapes along a schedule; returns false (with an error message) on an invalid one.
+struct OimPlan {
+    int n;
+    int h[kMaxPasses + 1], w[kMaxPasses + 1];     // grid before pass i (and after the last one)
+};
+
+static bool walk_schedule(int B, int H, int W, int D, const luvc_oim_pass* passes, int n_passes, OimPlan* pl)
+{
+    if (B < 1 || H < 1 || W < 1 || D < 1) { set_error("B, H, W, D must be positive (got %d,%d,%d,%d)", B, H, W, D); return false; }
+    if ((int64_t)B * H * W >= ((int64_t)1 << 31)) { set_error("B*H*W must stay below 2^31"); return false; }
+    if (!passes || n_passes < 1 || n_passes > kMaxPasses) { set_error("need 1..%d passes", kMaxPasses); return false; }
+    pl->n = n_passes;
+    pl->h[0] = H;
+    pl->w[0] = W;
+    for (int i = 0; i < n_passes; ++i) {
+        const int axis = passes[i].axis, m = passes[i].m;
+        if (axis != 0 && axis != 1) { set_error("pass %d: axis must be 0 (H) or 1 (W)", i); return false; }
+        const int len = axis ? pl->w[i] : pl->h[i];
+        if (len > kMaxLineLen) { set_error("pass %d: line length %d exceeds %d", i, len, kMaxLineLen); return false; }
+        if (m < 0 || m > (len + 1) / 2 || len - m < 1) {
+            set_error("pass %d: m=%d is outside 0..ceil(%d/2) or leaves no token", i, m, len);
+            return false;
+        }
+        pl->h[i + 1] = axis ? pl->h[i] : pl->h[i] - m;
+        pl->w[i + 1] = axis ? pl->w[i] - m : pl->w[i];
+    }
+    return true;
+}
+
+struct OimLayout {
+    size_t xbuf[2], sbuf[2], kbuf[2], maps[kMaxPasses], n2, dn, anchor, absorb, bytes;
+};
+
+static OimLayout oim_layout(int B, int D, luvc_dtype dt, const OimPlan& pl)
+{
+    OimLayout L{};
+    size_t off = 0;
+    // ping-pong buffers for the outputs of all passes but the last: pass i writes buffer i & 1
+    size_t tok[2] = {0, 0};
+    for (int i = 0; i + 1 < pl.n; ++i) {
+        const size_t t = (size_t)B * pl.h[i + 1] * pl.w[i + 1];
+        if (t > tok[i & 1]) tok[i & 1] = t;
+    }
+    for (int j = 0; j < 2; ++j) {
+        L.xbuf[j] = off; off += align_up(tok[j] * D * esize(dt));
+        L.sbuf[j] = off; off += align_up(tok[j] * sizeof(int32_t));
+        L.kbuf[j] = off; off += align_up(tok[j] * sizeof(int32_t));
+    }
+    size_t max_in = 0, max_out = 0;
+    for (int i = 0; i < pl.n; ++i) {
+        const size_t tin = (size_t)B * pl.h[i] * pl.w[i], tout = (size_t)B * pl.h[i + 1] * pl.w[i + 1];
+        L.maps[i] = off; off += align_up(tin * sizeof(int32_t));
+        if (tin > max_in) max_in = tin;
+        if (tout > max_out) max_out = tout;
+    }
+    L.n2 = off;     off += align_up(max_in * sizeof(double));
+    L.dn = off;     off += align_up(max_in * sizeof(double));
+    L.anchor = off; off += align_up(max_out * sizeof(int32_t));
+    L.absorb = off; off += align_up(max_out * sizeof(int32_t));
+    L.bytes = off;
+    return L;
+}
+
+static bool workspace_ok(const void* ws, size_t have, size_t need)
+{
+    if (need == 0) return true;
+    if (!ws) { set_error("workspace is NULL but %zu bytes are needed", need); return false; }
+    if ((uintptr_t)ws % 256 != 0) { set_error("workspace must be 256-byte aligned"); return false; }
+    if (have < need) { set_error("workspace holds %zu bytes, %zu are needed", have, need); return false; }
+    return true;
+}
+
+}  // namespace luvc
+
+using namespace luvc;
+
+extern "C" {
+
+const char* luvc_version(void) { return "libluvc 0.1 (gfx950)"; }
+
+const char* luvc_last_error(void) { return g_err; }
+
+luvc_status luvc_oim_plan(int H, int W, int64_t target_tokens, luvc_oim_pass* passes, int max_passes, int* n_passes)
+{
+    if (!passes || !n_passes || max_passes < 1) { set_error("passes / n_passes must be given"); return LUVC_ERR_INVALID_ARG; }
+    if (H < 1 || W < 1 || target_tokens < 1 || target_tokens > (int64_t)H * W) {
+        set_error("target_tokens must lie in 1..H*W");
+        return LUVC_ERR_INVALID_ARG;
+    }
+    int h = H, w = W, n = 0, axis = 1;
+    while ((int64_t)h * w > target_tokens) {
+        if (n >= max_passes) { set_error("schedule needs more than %d passes", max_passes); return LUVC_ERR_INVALID_ARG; }
+        int len = axis ? w : h;
+        const int other = axis ? h : w;
+        if (len == 1) {                      // nothing left on this axis: try the other one
+            axis ^= 1;
+            len = axis ? w : h;
+            if (len == 1) break;
+            continue;
+        }
+        int m = (len + 1) / 2;
+        if ((int64_t)(len - m) * other < target_tokens) {
+            // the exact m on this axis, if the other side divides the target
+            if (target_tokens % other != 0) { set_error("target %lld is not reachable from %dx%d", (long long)target_tokens, h, w); return LUVC_ERR_INVALID_ARG; }
+            m = len - (int)(target_tokens / other);
+        }
+        passes[n].axis = axis;
+        passes[n].m = m;
+        ++n;
+        if (axis) w -= m; else h -= m;
+        axis ^= 1;
+    }
+    if ((int64_t)h * w != target_tokens) { set_error("target %lld is not reachable", (long long)target_tokens); return LUVC_ERR_INVALID_ARG; }
+    *n_passes = n;
+    return LUVC_OK;
+}
+
+size_t luvc_oim_workspace_bytes(int B, int H, int W, int D, luvc_dtype dtype, const luvc_oim_pass* passes, int n_passes)
+{
+    OimPlan pl;
+    if (!dtype_ok(dtype) || !walk_schedule(B, H, W, D, passes, n_passes, &pl)) return 0;
+    return oim_layout(B, D, dtype, pl).bytes;
+}
+
+luvc_status luvc_oim_merge(const void* x, const int32_t* sizes_in, int B, int H, int W, int D, luvc_dtype dtype,
+                           const luvc_oim_pass* passes, int n_passes, int64_t target_tokens,
+                           void* x_out, int32_t* sizes_out, int32_t* merged_map, int32_t* kept_map,
+                           void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    if (!dtype_ok(dtype)) { set_error("unknown dtype %d", (int)dtype); return LUVC_ERR_INVALID_ARG; }
+    if (!x || !x_out || !sizes_out) { set_error("x, x_out and sizes_out must not be NULL"); return LUVC_ERR_INVALID_ARG; }
+    OimPlan pl;
+    if (!walk_schedule(B, H, W, D, passes, n_passes, &pl)) return LUVC_ERR_INVALID_ARG;
+    const int Ho = pl.h[pl.n], Wo = pl.w[pl.n];
+    if (target_tokens != 0 && target_tokens != (int64_t)Ho * Wo) {
+        set_error("schedule ends at %dx%d = %lld tokens, target is %lld", Ho, Wo, (long long)Ho * Wo, (long long)target_tokens);
+        return LUVC_ERR_INVALID_ARG;
+    }
+    const OimLayout L = oim_layout(B, D, dtype, pl);
+    if (!workspace_ok(workspace, workspace_bytes, L.bytes)) return LUVC_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)hip_stream;
+    char* ws = (char*)workspace;
+    const size_t es = esize(dtype);
+    // 16-byte accesses need aligned rows in every buffer the kernels touch
+    const bool vec = ((size_t)D * es) % 16 == 0 && (uintptr_t)x % 16 == 0 && (uintptr_t)x_out % 16 == 0;
+
+    OimScratch sc;
+    sc.n2 = (double*)(ws + L.n2);
+    sc.dn = (double*)(ws + L.dn);
+    sc.anchor = (int32_t*)(ws + L.anchor);
+    sc.absorb = (int32_t*)(ws + L.absorb);
+
+    const void* cur_x = x;
+    const int32_t* cur_s = sizes_in;
+    const int32_t* cur_k = nullptr;
+    const int32_t* maps[kMaxPasses];
+    int32_t n_in[kMaxPasses];
+    for (int i = 0; i < pl.n; ++i) {
+        const bool last = i + 1 == pl.n;
+        void* ox = last ? x_out : (void*)(ws + L.xbuf[i & 1]);
+        int32_t* os = last ? sizes_out : (int32_t*)(ws + L.sbuf[i & 1]);
+        int32_t* ok = last ? kept_map : (int32_t*)(ws + L.kbuf[i & 1]);
+        int32_t* pm = (int32_t*)(ws + L.maps[i]);
+        maps[i] = pm;
+        n_in[i] = pl.h[i] * pl.w[i];
+        const luvc_status rc = oim_general_pass(cur_x, cur_s, B, pl.h[i], pl.w[i], D, dtype, passes[i].axis, passes[i].m, vec,
+                                                ox, os, pm, cur_k, ok, sc, st);
+        if (rc != LUVC_OK) return rc;
+        cur_x = ox;
+        cur_s = os;
+        cur_k = ok;
+    }
+    if (merged_map) return oim_compose(maps, n_in, pl.n, B, H * W, merged_map, st);
+    return LUVC_OK;
+}
+
+size_t luvc_spu_workspace_bytes(int B, int N, int D, luvc_dtype dtype, int sigma)
+{
+    if (!dtype_ok(dtype) || B < 1 || N < 1 || D < 1 || sigma < 0 || sigma > N / 2 || N > kSpuMaxN) return 0;
+    return spu_layout(B, N, D, sigma).bytes;
+}
+
+luvc_status luvc_spu_score(const void* x, int B, int N, int D, int64_t row_stride, luvc_dtype dtype, int sigma,
+                           int use_hamming, float* scores, void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    if (!dtype_ok(dtype)) { set_error("unknown dtype %d", (int)dtype); return LUVC_ERR_INVALID_ARG; }
+    if (!x || !scores) { set_error("x and scores must not be NULL"); return LUVC_ERR_INVALID_ARG; }
+    if (B < 1 || N < 1 || D < 1) { set_error("B, N, D must be positive (got %d,%d,%d)", B, N, D); return LUVC_ERR_INVALID_ARG; }
+    if (row_stride < D) { set_error("row_stride %lld is smaller than D=%d", (long long)row_stride, D); return LUVC_ERR_INVALID_ARG; }
+    if (sigma < 0 || sigma > N / 2) { set_error("sigma=%d must lie in 0..N/2=%d", sigma, N / 2); return LUVC_ERR_INVALID_ARG; }
+    if (N > kSpuMaxN) { set_error("N=%d exceeds the supported %d tokens per sample", N, kSpuMaxN); return LUVC_ERR_UNSUPPORTED; }
+    if (B > 65535) { set_error("B=%d exceeds 65535 samples per call", B); return LUVC_ERR_UNSUPPORTED; }
+    const size_t need = spu_layout(B, N, D, sigma).bytes;
+    if (!workspace_ok(workspace, workspace_bytes, need)) return LUVC_ERR_WORKSPACE;
+    return spu_score_dense(x, B, N, D, row_stride, dtype, sigma, use_hamming ? 1 : 0, scores, workspace, (hipStream_t)hip_stream);
+}
+
+int luvc_keep_count(int N, double keep_ratio)
+{
+    if (N < 1) return 0;
+    double v = std::floor(keep_ratio * (double)N + 0.5);
+    if (!(v >= 1.0)) v = 1.0;
+    if (v > (double)N) v = (double)N;
+    return (int)v;
+}
+
+luvc_status luvc_spu_prune(const void* x, const float* scores, int B, int N, int D, int64_t row_stride, luvc_dtype dtype,
+                           int n_keep, int32_t* kept_idx, void* x_out, void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    (void)workspace;
+    (void)workspace_bytes;
+    if (!dtype_ok(dtype)) { set_error("unknown dtype %d", (int)dtype); return LUVC_ERR_INVALID_ARG; }
+    if (!scores || !kept_idx) { set_error("scores and kept_idx must not be NULL"); return LUVC_ERR_INVALID_ARG; }
+    if (x_out && !x) { set_error("x_out given without x"); return LUVC_ERR_INVALID_ARG; }
+    if (B < 1 || N < 1 || D < 1) { set_error("B, N, D must be positive (got %d,%d,%d)", B, N, D); return LUVC_ERR_INVALID_ARG; }
+    if (row_stride < D) { set_error("row_stride %lld is smaller than D=%d", (long long)row_stride, D); return LUVC_ERR_INVALID_ARG; }
+    if (n_keep < 1 || n_keep > N) { set_error("n_keep=%d must lie in 1..N=%d", n_keep, N); return LUVC_ERR_INVALID_ARG; }
+    if ((int64_t)B * N >= ((int64_t)1 << 31)) { set_error("B*N must stay below 2^31"); return LUVC_ERR_UNSUPPORTED; }
+    return spu_prune_run(x, scores, B, N, D, row_stride, dtype, n_keep, kept_idx, x_out, (hipStream_t)hip_stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,84 @@
+// Device-side helpers shared by the gfx950 kernels of libluvc: storage-type access, wave64
+// reductions, error plumbing.  Nothing here is shared with the CPU oracle.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/luvc.h"
+
+namespace luvc {
+
+constexpr int kWave = 64;
+
+// ------------------------------------------------------------------ host-side error text
+void set_error(const char* fmt, ...);
+luvc_status check_launch(const char* what);
+
+static inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
+
+// ------------------------------------------------------------------ storage types
+struct bf16_t { uint16_t bits; };
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+// round-to-nearest-even fp32 -> bf16 (NaN kept quiet)
+__device__ __forceinline__ uint16_t f32_to_bf16(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+// fp64 -> bf16 with a single rounding (round-to-odd into fp32 first, then nearest-even):
+// a value computed in fp64 lands on the same bf16 as the exact result would.
+__device__ __forceinline__ uint16_t f64_to_bf16(double v)
+{
+    float f = (float)v;                                   // nearest-even
+    if (isfinite(f) && (double)f != v) {                  // inexact: force the sticky (odd) bit
+        uint32_t u = __float_as_uint(f);
+        const bool away = fabs((double)f) > fabs(v);      // f was rounded away from zero
+        if (away) u -= 1;                                 // truncate toward zero ...
+        u |= 1u;                                          // ... and mark inexact
+        f = __uint_as_float(u);
+    }
+    return f32_to_bf16(f);
+}
+
+template <typename T> struct io_traits;
+template <> struct io_traits<float> {
+    static constexpr int kVec = 4;                        // elements per 16-byte access
+    using vec_t = float4;
+    __device__ static __forceinline__ float load(const float* p) { return *p; }
+    __device__ static __forceinline__ void store(float* p, double v) { *p = (float)v; }
+    __device__ static __forceinline__ void unpack(const vec_t& v, float* o) { o[0] = v.x; o[1] = v.y; o[2] = v.z; o[3] = v.w; }
+};
+template <> struct io_traits<bf16_t> {
+    static constexpr int kVec = 8;
+    using vec_t = uint4;
+    __device__ static __forceinline__ float load(const bf16_t* p) { return bf16_to_f32(p->bits); }
+    __device__ static __forceinline__ void store(bf16_t* p, double v) { p->bits = f64_to_bf16(v); }
+    __device__ static __forceinline__ void unpack(const vec_t& v, float* o)
+    {
+        o[0] = __uint_as_float(v.x << 16); o[1] = __uint_as_float(v.x & 0xffff0000u);
+        o[2] = __uint_as_float(v.y << 16); o[3] = __uint_as_float(v.y & 0xffff0000u);
+        o[4] = __uint_as_float(v.z << 16); o[5] = __uint_as_float(v.z & 0xffff0000u);
+        o[6] = __uint_as_float(v.w << 16); o[7] = __uint_as_float(v.w & 0xffff0000u);
+    }
+};
+
+// ------------------------------------------------------------------ wave64 reductions (all lanes get the result)
+__device__ __forceinline__ double wave_sum(double v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+    return v;
+}
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+    return v;
+}
+
+}  // namespace luvc

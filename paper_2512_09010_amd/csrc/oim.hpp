@@ -1,0 +1,26 @@
+// Internal interface between the C-ABI layer and the OIM kernels.
+#pragma once
+#include "common.hpp"
+
+namespace luvc {
+
+constexpr int kMaxPasses = 16;      // passes per luvc_oim_merge call
+constexpr int kMaxLineLen = 8192;   // tokens on one line (bounded by the decision kernel's LDS use)
+
+// Scratch of one pass, carved from the caller's workspace.
+struct OimScratch {
+    double* n2;        // [B*H*W] squared norms
+    double* dn;        // [B*H*W] dot product with the next token on the line
+    int32_t* anchor;   // [B*Ho*Wo]
+    int32_t* absorb;   // [B*Ho*Wo]
+};
+
+luvc_status oim_general_pass(const void* x, const int32_t* sizes_in, int B, int H, int W, int D, luvc_dtype dt,
+                             int axis, int m, bool vec, void* x_out, int32_t* sizes_out, int32_t* pass_map,
+                             const int32_t* kept_prev, int32_t* kept_out,
+                             const OimScratch& ws, hipStream_t st);
+
+luvc_status oim_compose(const int32_t* const* maps, const int32_t* n_in, int n, int B, int n_first,
+                        int32_t* merged_out, hipStream_t st);
+
+}  // namespace luvc

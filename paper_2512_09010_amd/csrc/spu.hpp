@@ -1,0 +1,22 @@
+// Internal interface between the C-ABI layer and the SPU kernels.
+#pragma once
+#include "common.hpp"
+
+namespace luvc {
+
+constexpr int kSpuMaxN = 32768;     // tokens per sample (twiddle index arithmetic stays in int32)
+
+// Offsets (bytes) of the score kernels' scratch inside the caller's workspace.
+struct SpuLayout {
+    size_t tw, gk, Fc, Fs, partial, bytes;
+    int n_tiles;
+};
+SpuLayout spu_layout(int B, int N, int D, int sigma);
+
+luvc_status spu_score_dense(const void* x, int B, int N, int D, int64_t row_stride, luvc_dtype dt, int sigma,
+                            int use_hamming, float* scores, void* workspace, hipStream_t st);
+
+luvc_status spu_prune_run(const void* x, const float* scores, int B, int N, int D, int64_t row_stride, luvc_dtype dt,
+                          int n_keep, int32_t* kept_idx, void* x_out, hipStream_t st);
+
+}  // namespace luvc

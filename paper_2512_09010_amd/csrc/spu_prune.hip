@@ -1,0 +1,151 @@
+// SPU prune (paper Algorithm 2, last two steps): order-preserving top-k keep and gather.
+//
+//   spu_select   one workgroup per sample.  Scores are mapped to unsigned keys whose integer order
+//                is the float order; a most-significant-digit radix select (4 passes of 8 bits,
+//                histogram in LDS) finds the key T of the n_keep-th largest score and how many
+//                tokens with key == T still belong to the keep set; a stable block-wide compaction
+//                then emits, in ascending index order, every token with key > T and the first of
+//                those with key == T (equal scores: the lower index wins).
+//   spu_gather   one wavefront per kept token copies the ORIGINAL row.
+#include "common.hpp"
+#include "spu.hpp"
+
+namespace luvc {
+
+__device__ __forceinline__ uint32_t score_key(float s)
+{
+    uint32_t u = __float_as_uint(s);
+    if (u == 0x80000000u) u = 0;                      // -0 and +0 compare equal
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+constexpr int kSelThreads = 1024;
+
+// inclusive block scan of one int per thread; returns the inclusive prefix, *total gets the block sum
+__device__ __forceinline__ int block_scan_incl(int v, int* wave_tot /*[16]*/, int* total)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int s = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int t = __shfl_up(s, o, kWave);
+        if (lane >= o) s += t;
+    }
+    __syncthreads();                                   // wave_tot may still be read from a previous scan
+    if (lane == 63) wave_tot[wave] = s;
+    __syncthreads();
+    int base = 0, tot = 0;
+    const int nw = blockDim.x >> 6;
+    for (int w = 0; w < nw; ++w) {
+        const int t = wave_tot[w];
+        if (w < wave) base += t;
+        tot += t;
+    }
+    *total = tot;
+    return s + base;
+}
+
+__global__ void __launch_bounds__(kSelThreads)
+spu_select(const float* __restrict__ scores, int N, int n_keep, int32_t* __restrict__ kept_idx)
+{
+    __shared__ int hist[256];
+    __shared__ int wave_tot[16];
+    __shared__ uint32_t sh_prefix;
+    __shared__ int sh_remaining;
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const float* s = scores + (int64_t)b * N;
+    int32_t* out = kept_idx + (int64_t)b * n_keep;
+
+    uint32_t prefix = 0, mask = 0;
+    int remaining = n_keep;                            // still to pick among keys matching the prefix
+    for (int shift = 24; shift >= 0; shift -= 8) {
+        if (tid < 256) hist[tid] = 0;
+        __syncthreads();
+        for (int n = tid; n < N; n += blockDim.x) {
+            const uint32_t k = score_key(s[n]);
+            if ((k & mask) == prefix) atomicAdd(&hist[(k >> shift) & 255u], 1);
+        }
+        __syncthreads();
+        if (tid == 0) {
+            int above = 0, bin = 255;
+            for (; bin > 0; --bin) {                   // largest digit first
+                const int h = hist[bin];
+                if (above + h >= remaining) break;
+                above += h;
+            }
+            sh_prefix = prefix | ((uint32_t)bin << shift);
+            sh_remaining = remaining - above;
+        }
+        __syncthreads();
+        prefix = sh_prefix;
+        remaining = sh_remaining;
+        mask |= 255u << shift;
+        __syncthreads();
+    }
+    const uint32_t T = prefix;                         // key of the n_keep-th largest score
+    const int take_eq = remaining;                     // tokens with key == T that are kept (lowest indices)
+
+    int eq_before = 0, sel_before = 0;
+    for (int n0 = 0; n0 < N; n0 += blockDim.x) {
+        const int n = n0 + tid;
+        uint32_t k = 0;
+        bool eq = false, gt = false;
+        if (n < N) { k = score_key(s[n]); eq = (k == T); gt = (k > T); }
+        int tot_eq, tot_sel;
+        const int eq_incl = block_scan_incl(eq ? 1 : 0, wave_tot, &tot_eq);
+        const bool sel = gt || (eq && (eq_before + eq_incl - 1) < take_eq);
+        const int sel_incl = block_scan_incl(sel ? 1 : 0, wave_tot, &tot_sel);
+        if (sel) {
+            const int q = sel_before + sel_incl - 1;
+            if (q < n_keep) out[q] = n;
+        }
+        eq_before += tot_eq;
+        sel_before += tot_sel;
+    }
+}
+
+template <int BYTES>   // 16: vector rows, 4 / 2: element rows
+__global__ void __launch_bounds__(256)
+spu_gather(const unsigned char* __restrict__ x, const int32_t* __restrict__ kept_idx, int N, int n_keep,
+           int64_t row_bytes_in, int64_t row_bytes_out, int64_t n_rows, unsigned char* __restrict__ x_out)
+{
+    const int64_t row = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int lane = threadIdx.x & 63;
+    if (row >= n_rows) return;
+    const int64_t b = row / n_keep;
+    int src = kept_idx[row];
+    src = src < 0 ? 0 : (src >= N ? N - 1 : src);      // indices come from spu_select; stay in bounds regardless
+    const unsigned char* in = x + (b * N + src) * row_bytes_in;
+    unsigned char* o = x_out + row * row_bytes_out;
+    if (BYTES == 16) {
+        for (int64_t i = (int64_t)lane * 16; i < row_bytes_out; i += 64 * 16)
+            *reinterpret_cast<uint4*>(o + i) = *reinterpret_cast<const uint4*>(in + i);
+    } else if (BYTES == 4) {
+        for (int64_t i = (int64_t)lane * 4; i < row_bytes_out; i += 64 * 4)
+            *reinterpret_cast<uint32_t*>(o + i) = *reinterpret_cast<const uint32_t*>(in + i);
+    } else {
+        for (int64_t i = (int64_t)lane * 2; i < row_bytes_out; i += 64 * 2)
+            *reinterpret_cast<uint16_t*>(o + i) = *reinterpret_cast<const uint16_t*>(in + i);
+    }
+}
+
+luvc_status spu_prune_run(const void* x, const float* scores, int B, int N, int D, int64_t row_stride, luvc_dtype dt,
+                          int n_keep, int32_t* kept_idx, void* x_out, hipStream_t st)
+{
+    hipLaunchKernelGGL(spu_select, dim3((unsigned)B), dim3(kSelThreads), 0, st, scores, N, n_keep, kept_idx);
+    if (x_out) {
+        const int es = dt == LUVC_F32 ? 4 : 2;
+        const int64_t rin = row_stride * es, rout = (int64_t)D * es, rows = (int64_t)B * n_keep;
+        const unsigned g = (unsigned)((rows * 64 + 255) / 256);
+        const bool v16 = rin % 16 == 0 && rout % 16 == 0 && ((uintptr_t)x % 16 == 0) && ((uintptr_t)x_out % 16 == 0);
+        if (v16)
+            hipLaunchKernelGGL((spu_gather<16>), dim3(g), dim3(256), 0, st, (const unsigned char*)x, kept_idx, N, n_keep, rin, rout, rows, (unsigned char*)x_out);
+        else if (es == 4)
+            hipLaunchKernelGGL((spu_gather<4>), dim3(g), dim3(256), 0, st, (const unsigned char*)x, kept_idx, N, n_keep, rin, rout, rows, (unsigned char*)x_out);
+        else
+            hipLaunchKernelGGL((spu_gather<2>), dim3(g), dim3(256), 0, st, (const unsigned char*)x, kept_idx, N, n_keep, rin, rout, rows, (unsigned char*)x_out);
+    }
+    return check_launch("spu prune");
+}
+
+}  // namespace luvc

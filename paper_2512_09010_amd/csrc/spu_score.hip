@@ -1,0 +1,172 @@
+// SPU score (paper Section 3.3, Eq. 4-8): direct pass-band DFT path, valid for any N.
+//
+// The mask of Eq. 5 is real and symmetric in k, so for a real signal x[n] the filtered signal is
+//     x'[n] = sum_{k=0..sigma} g_k ( C_k cos(2 pi k n / N) + S_k sin(2 pi k n / N) ),
+//     C_k = sum_n x[n] cos(2 pi k n / N),  S_k = sum_n x[n] sin(2 pi k n / N),
+//     g_0 = M[0]/N,  g_k = 2 M[k]/N  (g_k = M[k]/N when 2k = N, the self-mirrored bin),
+// i.e. Eq. 4 evaluated on the pass-band bins only (all other bins are multiplied by zero in Eq. 6)
+// and Eq. 7 with the +k / -k terms paired.  Lanes of a wavefront are channels, so twiddles are
+// wave-uniform and come through the scalar path; token rows are read coalesced.
+//
+//   spu_tables      twiddles (fp64 sincospi rounded to fp32) and the weights g_k
+//   spu_fwd_dense   C_k, S_k for a tile of 64 channels and a group of bins
+//   spu_inv_dense   x'[n] for a tile of 64 channels and a chunk of tokens, squared and summed over the tile
+//   spu_finish      fixed-order sum over channel tiles, square root (Eq. 8)
+#include "common.hpp"
+#include "spu.hpp"
+
+namespace luvc {
+
+__global__ void __launch_bounds__(256)
+spu_tables(int N, int sigma, int use_hamming, float2* __restrict__ tw, float* __restrict__ gk)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < N) {
+        double s, c;
+        sincospi(2.0 * (double)i / (double)N, &s, &c);
+        tw[i] = make_float2((float)c, (float)s);
+    }
+    if (i <= sigma) {
+        double w = 1.0;
+        if (use_hamming && N > 1) w = 0.54 + 0.46 * cospi(2.0 * (double)i / (double)(N - 1));
+        const double pair = (i == 0 || 2 * i == N) ? 1.0 : 2.0;
+        gk[i] = (float)(pair * w / (double)N);
+    }
+}
+
+constexpr int kKPW = 8;    // bins per wavefront in the forward kernel
+constexpr int kNB = 8;     // tokens per register block in the inverse kernel
+constexpr int kNChunk = 128;  // tokens per workgroup in the inverse kernel (4 waves x 4 blocks x kNB)
+
+template <typename T>
+__global__ void __launch_bounds__(256)
+spu_fwd_dense(const T* __restrict__ x, int N, int D, int64_t row_stride, int sigma,
+              const float2* __restrict__ tw, float* __restrict__ Fc, float* __restrict__ Fs)
+{
+    using tr = io_traits<T>;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int d = blockIdx.x * 64 + lane;
+    const int b = blockIdx.z;
+    const int k0 = (blockIdx.y * 4 + wave) * kKPW;
+    if (k0 > sigma) return;
+    const bool live = d < D;
+    const T* xb = x + (int64_t)b * N * row_stride + (live ? d : 0);
+    float ac[kKPW], as[kKPW];
+    int idx[kKPW], kstep[kKPW];
+#pragma unroll
+    for (int j = 0; j < kKPW; ++j) { ac[j] = 0.f; as[j] = 0.f; idx[j] = 0; kstep[j] = (k0 + j <= sigma) ? k0 + j : 0; }
+    for (int n = 0; n < N; ++n) {
+        const float xv = live ? tr::load(xb + (int64_t)n * row_stride) : 0.f;
+#pragma unroll
+        for (int j = 0; j < kKPW; ++j) {
+            const float2 t = tw[idx[j]];
+            ac[j] = fmaf(xv, t.x, ac[j]);
+            as[j] = fmaf(xv, t.y, as[j]);
+            idx[j] += kstep[j];                    // (k * n) mod N, kept incrementally (k <= sigma < N)
+            if (idx[j] >= N) idx[j] -= N;
+        }
+    }
+    if (!live) return;
+#pragma unroll
+    for (int j = 0; j < kKPW; ++j) {
+        const int k = k0 + j;
+        if (k <= sigma) {
+            Fc[((int64_t)b * (sigma + 1) + k) * D + d] = ac[j];
+            Fs[((int64_t)b * (sigma + 1) + k) * D + d] = as[j];
+        }
+    }
+}
+
+__global__ void __launch_bounds__(256)
+spu_inv_dense(const float* __restrict__ Fc, const float* __restrict__ Fs, int N, int D, int sigma,
+              const float2* __restrict__ tw, const float* __restrict__ gk,
+              float* __restrict__ partial /* [B, n_tiles, N] */)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int tile = blockIdx.x, n_tiles = gridDim.x;
+    const int d = tile * 64 + lane;
+    const int b = blockIdx.z;
+    const bool live = d < D;
+    const float* fc = Fc + (int64_t)b * (sigma + 1) * D + (live ? d : 0);
+    const float* fs = Fs + (int64_t)b * (sigma + 1) * D + (live ? d : 0);
+    for (int blk = 0; blk < kNChunk / (4 * kNB); ++blk) {
+        const int n0 = blockIdx.y * kNChunk + (blk * 4 + wave) * kNB;
+        if (n0 >= N) break;
+        float acc[kNB];
+        int idx[kNB], stepn[kNB];
+#pragma unroll
+        for (int j = 0; j < kNB; ++j) { acc[j] = 0.f; idx[j] = 0; stepn[j] = (n0 + j) % N; }
+        for (int k = 0; k <= sigma; ++k) {
+            const float g = gk[k];
+            const float c = live ? g * fc[(int64_t)k * D] : 0.f;
+            const float s = live ? g * fs[(int64_t)k * D] : 0.f;
+#pragma unroll
+            for (int j = 0; j < kNB; ++j) {
+                const float2 t = tw[idx[j]];
+                acc[j] = fmaf(c, t.x, acc[j]);
+                acc[j] = fmaf(s, t.y, acc[j]);
+                idx[j] += stepn[j];                // (k * n) mod N
+                if (idx[j] >= N) idx[j] -= N;
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < kNB; ++j) {
+            const float e = wave_sum(acc[j] * acc[j]);
+            if (lane == 0 && n0 + j < N) partial[((int64_t)b * n_tiles + tile) * N + n0 + j] = e;
+        }
+    }
+}
+
+__global__ void __launch_bounds__(256)
+spu_finish(const float* __restrict__ partial, int N, int n_tiles, int64_t total, float* __restrict__ scores)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= total) return;
+    const int64_t b = i / N;
+    const int n = (int)(i - b * N);
+    double e = 0.0;
+    for (int t = 0; t < n_tiles; ++t) e += (double)partial[(b * n_tiles + t) * N + n];
+    scores[i] = (float)sqrt(e);
+}
+
+// ------------------------------------------------------------------ host side
+SpuLayout spu_layout(int B, int N, int D, int sigma)
+{
+    SpuLayout L;
+    L.n_tiles = (D + 63) / 64;
+    size_t off = 0;
+    L.tw = off;      off += align_up(sizeof(float2) * (size_t)N);
+    L.gk = off;      off += align_up(sizeof(float) * (size_t)(sigma + 1));
+    L.Fc = off;      off += align_up(sizeof(float) * (size_t)B * (sigma + 1) * D);
+    L.Fs = off;      off += align_up(sizeof(float) * (size_t)B * (sigma + 1) * D);
+    L.partial = off; off += align_up(sizeof(float) * (size_t)B * L.n_tiles * N);
+    L.bytes = off;
+    return L;
+}
+
+luvc_status spu_score_dense(const void* x, int B, int N, int D, int64_t row_stride, luvc_dtype dt, int sigma,
+                            int use_hamming, float* scores, void* workspace, hipStream_t st)
+{
+    const SpuLayout L = spu_layout(B, N, D, sigma);
+    char* ws = (char*)workspace;
+    float2* tw = (float2*)(ws + L.tw);
+    float* gk = (float*)(ws + L.gk);
+    float* Fc = (float*)(ws + L.Fc);
+    float* Fs = (float*)(ws + L.Fs);
+    float* partial = (float*)(ws + L.partial);
+    hipLaunchKernelGGL(spu_tables, dim3((unsigned)((N + 255) / 256)), dim3(256), 0, st, N, sigma, use_hamming, tw, gk);
+    const dim3 gf((unsigned)L.n_tiles, (unsigned)((sigma + 1 + 4 * kKPW - 1) / (4 * kKPW)), (unsigned)B);
+    if (dt == LUVC_F32)
+        hipLaunchKernelGGL((spu_fwd_dense<float>), gf, dim3(256), 0, st, (const float*)x, N, D, row_stride, sigma, tw, Fc, Fs);
+    else
+        hipLaunchKernelGGL((spu_fwd_dense<bf16_t>), gf, dim3(256), 0, st, (const bf16_t*)x, N, D, row_stride, sigma, tw, Fc, Fs);
+    const dim3 gi((unsigned)L.n_tiles, (unsigned)((N + kNChunk - 1) / kNChunk), (unsigned)B);
+    hipLaunchKernelGGL(spu_inv_dense, gi, dim3(256), 0, st, Fc, Fs, N, D, sigma, tw, gk, partial);
+    const int64_t total = (int64_t)B * N;
+    hipLaunchKernelGGL(spu_finish, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, partial, N, L.n_tiles, total, scores);
+    return check_launch("spu score");
+}
+
+}  // namespace luvc

@@ -1,0 +1,137 @@
+"""Host-side checks of the C ABI: the library loads, exports every symbol the header declares,
+and rejects bad arguments before touching any device (so these run without a GPU)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2512_09010_amd import binding as lv
+from paper_2512_09010_amd import build as lvbuild
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    lvbuild.build(force=False)
+    return lv.lib()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "luvc.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(luvc_[a-z_]+)\s*\(", text)))
+
+
+def test_exports_match_header(L):
+    names = declared_symbols()
+    assert set(names) == set(lv.EXPORTS)
+    for n in names:
+        assert hasattr(L, n), n
+    assert b"gfx950" in L.luvc_version()
+
+
+def test_keep_count(L):
+    assert lv.luvc_keep_count(1024, 0.20) == 205
+    assert lv.luvc_keep_count(196, 0.05) == 10
+    assert lv.luvc_keep_count(144, 0.25) == 36
+    assert lv.luvc_keep_count(720, 0.15) == 108
+    assert lv.luvc_keep_count(2048, 0.10) == 205
+    assert lv.luvc_keep_count(10, 0.0) == 1 and lv.luvc_keep_count(10, 3.0) == 10
+    assert lv.luvc_keep_count(0, 0.5) == 0
+
+
+def test_plan(L):
+    assert lv.luvc_oim_plan(24, 24, 144) == [(1, 12), (0, 12)]
+    assert lv.luvc_oim_plan(64, 64, 1024) == [(1, 32), (0, 32)]
+    assert lv.luvc_oim_plan(112, 112, 196) == [(1, 56), (0, 56), (1, 28), (0, 28), (1, 14), (0, 14)]
+    assert lv.luvc_oim_plan(16, 16, 16 * 14) == [(1, 2)]            # the paper's merge number 2 on one axis
+    assert lv.luvc_oim_plan(8, 8, 64) == []
+    assert lv.luvc_oim_plan(9, 7, 4 * 3) == [(1, 4), (0, 5)]          # odd lines: every source merges (ceil)
+    with pytest.raises(lv.LuvcError):
+        lv.luvc_oim_plan(16, 16, 255)                                # 255 is no multiple of 16
+    with pytest.raises(lv.LuvcError):
+        lv.luvc_oim_plan(16, 16, 0)
+    with pytest.raises(lv.LuvcError):
+        lv.luvc_oim_plan(16, 16, 257)
+    # every plan lands exactly on its target
+    for H, W, t in [(24, 24, 144), (10, 6, 15), (7, 5, 6), (33, 17, 128), (33, 17, 20 * 8)]:
+        h, w = H, W
+        for axis, m in lv.luvc_oim_plan(H, W, t):
+            assert 0 < m <= ((w if axis else h) + 1) // 2
+            if axis:
+                w -= m
+            else:
+                h -= m
+        assert h * w == t
+
+
+def P(passes):
+    return lv._passes(passes), len(passes)
+
+
+def test_workspace_queries(L):
+    p, n = P([(1, 32), (0, 32)])
+    a = L.luvc_oim_workspace_bytes(8, 64, 64, 1280, lv.LUVC_BF16, p, n)
+    assert a > 8 * 64 * 32 * 1280 * 2 and a % 256 == 0
+    assert L.luvc_oim_workspace_bytes(8, 64, 64, 1280, 7, p, n) == 0
+    assert L.luvc_oim_workspace_bytes(0, 64, 64, 1280, lv.LUVC_BF16, p, n) == 0
+    bad, nb = P([(1, 33)])
+    assert L.luvc_oim_workspace_bytes(8, 64, 64, 1280, lv.LUVC_BF16, bad, nb) == 0
+    assert L.luvc_spu_workspace_bytes(8, 1024, 3584, lv.LUVC_BF16, 102) > 0
+    assert L.luvc_spu_workspace_bytes(8, 1024, 3584, lv.LUVC_BF16, 513) == 0
+    assert L.luvc_spu_workspace_bytes(8, 0, 3584, lv.LUVC_BF16, 0) == 0
+
+
+FAKE = ctypes.c_void_p(0x1000)          # never dereferenced: every call below must fail validation first
+
+
+def test_oim_merge_rejects_bad_arguments(L):
+    p, n = P([(1, 2), (0, 2)])
+    args = lambda **kw: [kw.get("x", FAKE), None, kw.get("B", 1), kw.get("H", 8), kw.get("W", 8), kw.get("D", 64),
+                         kw.get("dt", lv.LUVC_F32), kw.get("p", p), kw.get("n", n), kw.get("target", 0),
+                         kw.get("xo", FAKE), kw.get("so", FAKE), None, None, kw.get("ws", None), kw.get("wsb", 0), None]
+    assert L.luvc_oim_merge(*args(x=None)) == lv.LUVC_ERR_INVALID_ARG
+    assert L.luvc_oim_merge(*args(xo=None)) == lv.LUVC_ERR_INVALID_ARG
+    assert L.luvc_oim_merge(*args(so=None)) == lv.LUVC_ERR_INVALID_ARG
+    assert L.luvc_oim_merge(*args(B=0)) == lv.LUVC_ERR_INVALID_ARG
+    assert L.luvc_oim_merge(*args(D=-1)) == lv.LUVC_ERR_INVALID_ARG
+    assert L.luvc_oim_merge(*args(dt=5)) == lv.LUVC_ERR_INVALID_ARG
+    assert L.luvc_oim_merge(*args(n=0)) == lv.LUVC_ERR_INVALID_ARG
+    assert L.luvc_oim_merge(*args(n=99)) == lv.LUVC_ERR_INVALID_ARG
+    assert L.luvc_oim_merge(*args(target=35)) == lv.LUVC_ERR_INVALID_ARG       # schedule ends at 6x6 = 36
+    assert "36" in lv.last_error()
+    for bad in ([(1, 5)], [(2, 1)], [(1, -1)], [(1, 4), (1, 2), (1, 1), (1, 1)]):
+        bp, bn = P(bad)
+        assert L.luvc_oim_merge(*args(p=bp, n=bn)) == lv.LUVC_ERR_INVALID_ARG, bad
+    # valid arguments but no / short / misaligned workspace
+    assert L.luvc_oim_merge(*args()) == lv.LUVC_ERR_WORKSPACE
+    assert L.luvc_oim_merge(*args(ws=ctypes.c_void_p(0x10000), wsb=16)) == lv.LUVC_ERR_WORKSPACE
+    assert L.luvc_oim_merge(*args(ws=ctypes.c_void_p(0x10008), wsb=1 << 30)) == lv.LUVC_ERR_WORKSPACE
+    assert lv.last_error() != ""
+
+
+def test_spu_rejects_bad_arguments(L):
+    sc = lambda **kw: [kw.get("x", FAKE), kw.get("B", 2), kw.get("N", 64), kw.get("D", 128), kw.get("rs", 128),
+                       kw.get("dt", lv.LUVC_BF16), kw.get("sigma", 6), 1, kw.get("out", FAKE), kw.get("ws", None),
+                       kw.get("wsb", 0), None]
+    assert L.luvc_spu_score(*sc(x=None)) == lv.LUVC_ERR_INVALID_ARG
+    assert L.luvc_spu_score(*sc(out=None)) == lv.LUVC_ERR_INVALID_ARG
+    assert L.luvc_spu_score(*sc(N=0)) == lv.LUVC_ERR_INVALID_ARG
+    assert L.luvc_spu_score(*sc(rs=127)) == lv.LUVC_ERR_INVALID_ARG
+    assert L.luvc_spu_score(*sc(sigma=33)) == lv.LUVC_ERR_INVALID_ARG
+    assert L.luvc_spu_score(*sc(sigma=-1)) == lv.LUVC_ERR_INVALID_ARG
+    assert L.luvc_spu_score(*sc(dt=2)) == lv.LUVC_ERR_INVALID_ARG
+    assert L.luvc_spu_score(*sc(N=1 << 20, sigma=5)) == lv.LUVC_ERR_UNSUPPORTED
+    assert L.luvc_spu_score(*sc()) == lv.LUVC_ERR_WORKSPACE
+    pr = lambda **kw: [kw.get("x", FAKE), kw.get("s", FAKE), kw.get("B", 2), kw.get("N", 64), kw.get("D", 128),
+                       kw.get("rs", 128), kw.get("dt", lv.LUVC_BF16), kw.get("k", 8), kw.get("idx", FAKE),
+                       kw.get("xo", FAKE), None, 0, None]
+    assert L.luvc_spu_prune(*pr(s=None)) == lv.LUVC_ERR_INVALID_ARG
+    assert L.luvc_spu_prune(*pr(idx=None)) == lv.LUVC_ERR_INVALID_ARG
+    assert L.luvc_spu_prune(*pr(x=None)) == lv.LUVC_ERR_INVALID_ARG            # x_out without x
+    assert L.luvc_spu_prune(*pr(k=0)) == lv.LUVC_ERR_INVALID_ARG
+    assert L.luvc_spu_prune(*pr(k=65)) == lv.LUVC_ERR_INVALID_ARG
+    assert L.luvc_spu_prune(*pr(rs=4)) == lv.LUVC_ERR_INVALID_ARG
+    assert L.luvc_spu_prune(*pr(B=-3)) == lv.LUVC_ERR_INVALID_ARG

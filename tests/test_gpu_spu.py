@@ -1,0 +1,130 @@
+"""GPU parity: luvc_spu_score / luvc_spu_prune (through the C ABI) against the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2512_09010_amd import binding as lv
+from paper_2512_09010_amd import workloads as wl
+from gpu_util import SPU_MARGIN, to_dev, to_host_f64
+
+pytestmark = pytest.mark.gpu
+
+# fp32 arithmetic on both storage types: the scores themselves are held to the fp32 bar
+SCORE_RTOL = 1e-5
+
+
+def score_case(oracle, x_io, dtype, sigma, ham=True, tag="", stride_pad=0):
+    print(f"[spu] {tag} shape={x_io.shape} dtype={dtype} sigma={sigma} ham={ham}", flush=True)
+    ref = oracle.spu_score(wl.widen(x_io, dtype), sigma, ham)
+    xd = to_dev(x_io, dtype)
+    if stride_pad:
+        B, N, D = xd.shape
+        wide = torch.full((B, N, D + stride_pad), float("nan"), dtype=xd.dtype, device="cuda")
+        wide[:, :, :D] = xd
+        xd = wide[:, :, :D]
+    got = lv.luvc_spu_score(xd, sigma, ham)
+    torch.cuda.synchronize()
+    floor = 1e-6 * np.abs(ref).max()                # tokens whose filtered energy vanishes carry no relative meaning
+    g = got.cpu().numpy().astype(np.float64)
+    err = np.abs(g - ref)
+    assert (err <= SCORE_RTOL * np.abs(ref) + floor).all(), (tag, float((err / (np.abs(ref) + floor)).max()))
+    return xd, got, ref
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("B,N,D,sigma", [
+    (1, 1, 8, 0), (1, 2, 8, 1), (2, 5, 3, 2), (2, 16, 64, 3), (1, 97, 70, 10), (2, 144, 200, 18),
+    (1, 196, 130, 4), (1, 256, 64, 128), (2, 130, 65, 0), (1, 300, 96, 31),
+])
+def test_score_small_random(oracle, dtype, B, N, D, sigma):
+    rng = np.random.default_rng(N * 31 + D)
+    x = wl.cast_io(rng.standard_normal((B, N, D)).astype(np.float32), dtype)
+    score_case(oracle, x, dtype, sigma, True, "random")
+    score_case(oracle, x, dtype, sigma, False, "random-rect")
+
+
+def test_score_strided_rows(oracle):
+    rng = np.random.default_rng(3)
+    x = wl.cast_io(rng.standard_normal((2, 40, 72)).astype(np.float32), "bf16")
+    score_case(oracle, x, "bf16", 5, True, "strided", stride_pad=24)
+
+
+def test_score_special_signals(oracle):
+    N, D = 64, 64
+    n = np.arange(N)
+    const = np.broadcast_to(np.linspace(-1, 1, D, dtype=np.float32), (1, N, D)).copy()
+    _, got, ref = score_case(oracle, const, "f32", 6, True, "constant")
+    np.testing.assert_allclose(got.cpu().numpy(), np.linalg.norm(const[0, 0]), rtol=1e-5)
+    high = np.broadcast_to(np.cos(np.pi * n)[None, :, None].astype(np.float32), (1, N, D)).copy()
+    got = lv.luvc_spu_score(to_dev(high, "f32"), 6, False)
+    assert got.abs().max().item() < 1e-4 * np.sqrt(D)          # the Nyquist ripple is outside the pass-band
+
+
+@pytest.mark.parametrize("i", [0, 1, 2, 3, 4])
+def test_mini_workloads(oracle, i):
+    w = wl.mini(i)
+    x = wl.spu_input(w)
+    xd, got, ref = score_case(oracle, x, w.dtype, w.sigma, True, w.name)
+    n_keep = w.n_keep
+    assert n_keep == lv.luvc_keep_count(w.spu_N, w.keep_ratio) == oracle.keep_count(w.spu_N, w.keep_ratio)
+    pr = lv.luvc_spu_prune(xd, got, n_keep)
+    torch.cuda.synchronize()
+    kept = pr["kept_idx"].cpu().numpy()
+    # (i) the selection itself is exact: same answer as the oracle's selection on the GPU's own scores
+    own = oracle.spu_prune(got.cpu().numpy().astype(np.float64), n_keep)
+    np.testing.assert_array_equal(kept, own["kept_idx"])
+    # (ii) and equal to the oracle's keep set whenever its boundary gap exceeds the fp32 error of the scores
+    full = oracle.spu_prune(ref, n_keep, wl.widen(x, w.dtype))
+    if full["margin"] > SPU_MARGIN:
+        np.testing.assert_array_equal(kept, full["kept_idx"])
+        np.testing.assert_array_equal(to_host_f64(pr["x"]), full["x"])     # original tokens, bit copies
+    else:
+        print(f"keep boundary gap {full['margin']:.2e} below {SPU_MARGIN}: set compared on own scores only")
+
+
+def adversarial_scores(N, rng):
+    cases = [np.ones(N, np.float32), np.zeros(N, np.float32), np.arange(N, dtype=np.float32), np.arange(N, dtype=np.float32)[::-1].copy(),
+             np.round(rng.random(N).astype(np.float32) * 4) / 4,
+             rng.random(N).astype(np.float32),
+             np.where(rng.random(N) < 0.5, np.float32(0.0), np.float32(-0.0)).astype(np.float32),
+             (rng.random(N).astype(np.float32) * np.float32(1e-41)),                 # denormals
+             np.where(rng.random(N) < 0.1, np.float32(np.inf), rng.random(N).astype(np.float32)).astype(np.float32),
+             rng.standard_normal(N).astype(np.float32)]                              # negative values order correctly too
+    return np.stack(cases)
+
+
+@pytest.mark.parametrize("N,k", [(1, 1), (7, 3), (64, 64), (257, 1), (1024, 205), (2048, 205), (3000, 1500), (720, 108)])
+def test_select_against_stable_sort(oracle, N, k):
+    rng = np.random.default_rng(N + k)
+    sc = adversarial_scores(N, rng)
+    print(f"[select] N={N} k={k}", flush=True)
+    pr = lv.luvc_spu_prune(None, torch.from_numpy(sc).cuda(), k, gather=False)
+    torch.cuda.synchronize()
+    kept = pr["kept_idx"].cpu().numpy()
+    want = oracle.spu_prune(sc.astype(np.float64), k)["kept_idx"]
+    np.testing.assert_array_equal(kept, want)
+    assert (np.diff(kept, axis=1) > 0).all() if k > 1 else True
+
+
+def test_select_nonfinite_stays_well_formed():
+    N, k = 500, 100
+    sc = np.random.default_rng(0).standard_normal(N).astype(np.float32)
+    sc[::7] = np.nan
+    sc[3::11] = -np.inf
+    pr = lv.luvc_spu_prune(None, torch.from_numpy(sc[None]).cuda(), k, gather=False)
+    kept = pr["kept_idx"].cpu().numpy()[0]
+    assert len(np.unique(kept)) == k and (np.diff(kept) > 0).all() and kept.min() >= 0 and kept.max() < N
+
+
+@pytest.mark.parametrize("dtype,D,pad", [("f32", 33, 0), ("bf16", 33, 0), ("bf16", 64, 8), ("f32", 256, 4), ("bf16", 3584, 0)])
+def test_gather_rows(dtype, D, pad):
+    rng = np.random.default_rng(D)
+    B, N, k = 2, 50, 13
+    x = wl.cast_io(rng.standard_normal((B, N, D + pad)).astype(np.float32), dtype)
+    xd = to_dev(x, dtype)[:, :, :D]
+    sc = torch.from_numpy(rng.random((B, N)).astype(np.float32)).cuda()
+    pr = lv.luvc_spu_prune(xd, sc, k)
+    torch.cuda.synchronize()
+    idx = pr["kept_idx"].long()
+    want = torch.gather(xd, 1, idx[:, :, None].expand(B, k, D))
+    assert torch.equal(pr["x"].view(torch.int16) if dtype == "bf16" else pr["x"], want.contiguous().view(torch.int16) if dtype == "bf16" else want)
