@@ -1,0 +1,188 @@
+#!/usr/bin/env python3
+"""Throughput of the OIM + SPU hot path on one MI355X.
+
+A step = luvc_oim_merge (every call of the workload's schedule) + luvc_spu_score + luvc_spu_prune
+over one batch of seeded synthetic input that is already resident in HBM.  Prints ONE JSON line:
+tokens/s (visual tokens entering OIM per second), the HBM roofline of the dominant kernel measured
+with HIP events on the launch stream, and the CPU oracle timed on a bounded sample of the same
+workload on this host's cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=1, help="workload 0..4 of BASELINE.json (default 1: the metric's config)")
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
+    ap.add_argument("--rotate-mb", type=float, default=600.0, help="distinct input bytes cycled through (defeats cache reuse)")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU by design (the path shards over the batch with no exchange); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    from paper_2512_09010_amd import binding as lv
+    from paper_2512_09010_amd import workloads as wl
+
+    lv.lib()                                       # fail loudly if the HIP library is not built
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+    w = wl.workload(args.config)
+    tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+    es = 2 if w.dtype == "bf16" else 4
+
+    def upload(a):
+        if w.dtype == "bf16":
+            return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).view(torch.bfloat16).to(dev)
+        return torch.from_numpy(a).to(dev)
+
+    t0 = time.time()
+    x_oim_host = wl.oim_input(w)
+    x_spu_host = wl.spu_input(w)
+    x_oim0, x_spu0 = upload(x_oim_host), upload(x_spu_host)
+    set_bytes = x_oim0.numel() * es + x_spu0.numel() * es
+    n_rot = max(2, int(np.ceil(args.rotate_mb * 1e6 / set_bytes)))
+    xs_oim = [x_oim0] + [x_oim0.clone() for _ in range(n_rot - 1)]
+    xs_spu = [x_spu0] + [x_spu0.clone() for _ in range(n_rot - 1)]
+    gen_s = time.time() - t0
+
+    # ---- preallocate every output and workspace: nothing is allocated inside the timed region
+    code = lv.LUVC_BF16 if w.dtype == "bf16" else lv.LUVC_F32
+    calls = []
+    H, W = w.H, w.W
+    ws_bytes = 256
+    for passes in w.oim_calls:
+        Ho, Wo = lv.out_grid(H, W, passes)
+        out = dict(x=torch.empty((w.grids, Ho, Wo, w.D), dtype=tdt, device=dev),
+                   sizes=torch.empty((w.grids, Ho, Wo), dtype=torch.int32, device=dev),
+                   merged_map=torch.empty((w.grids, H * W), dtype=torch.int32, device=dev),
+                   kept_map=torch.empty((w.grids, Ho * Wo), dtype=torch.int32, device=dev))
+        ws_bytes = max(ws_bytes, lv.luvc_oim_workspace_bytes(w.grids, H, W, w.D, code, passes))
+        calls.append((passes, out))
+        H, W = Ho, Wo
+    ws_bytes = max(ws_bytes, lv.luvc_spu_workspace_bytes(w.spu_B, w.spu_N, w.spu_D, code, w.sigma))
+    workspace = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    scores = torch.empty((w.spu_B, w.spu_N), dtype=torch.float32, device=dev)
+    pr_out = dict(kept_idx=torch.empty((w.spu_B, w.n_keep), dtype=torch.int32, device=dev),
+                  x=torch.empty((w.spu_B, w.n_keep, w.spu_D), dtype=tdt, device=dev))
+    stream = torch.cuda.current_stream()
+
+    def step(i, ev=None):
+        x, sizes = xs_oim[i % n_rot], None
+        if ev: ev[0].record(stream)
+        for passes, out in calls:
+            lv.luvc_oim_merge(x, passes, sizes=sizes, workspace=workspace, stream=stream, out=out)
+            x, sizes = out["x"], out["sizes"]
+        if ev: ev[1].record(stream)
+        xs = xs_spu[i % n_rot]
+        lv.luvc_spu_score(xs, w.sigma, True, workspace=workspace, stream=stream, out=scores)
+        if ev: ev[2].record(stream)
+        lv.luvc_spu_prune(xs, scores, w.n_keep, stream=stream, out=pr_out)
+        if ev: ev[3].record(stream)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i, events[i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    seg = np.array([[e[j].elapsed_time(e[j + 1]) for j in range(3)] for e in events])      # ms: oim, score, prune
+    seg_mean = seg.mean(axis=0)
+    ms_per_step = wall * 1e3 / args.steps
+    tokens_per_s = w.tokens_in / (wall / args.steps)
+
+    # ---- algorithmic bytes: every input element read once, every output element written once
+    oim_bytes = 0
+    H, W = w.H, w.W
+    for passes, out in calls:
+        Ho, Wo = lv.out_grid(H, W, passes)
+        oim_bytes += w.grids * (H * W + Ho * Wo) * w.D * es
+        H, W = Ho, Wo
+    score_bytes = w.spu_B * w.spu_N * w.spu_D * es
+    prune_bytes = 2 * w.spu_B * w.n_keep * w.spu_D * es
+    alg = dict(oim=oim_bytes, spu_score=score_bytes, spu_prune=prune_bytes)
+    names = ["oim", "spu_score", "spu_prune"]
+    dom = int(np.argmax(seg_mean))
+    achieved = alg[names[dom]] / (seg_mean[dom] * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": names[dom], "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "algorithmic_bytes": alg[names[dom]], "avg_ms": round(float(seg_mean[dom]), 5),
+                "whole_step": {"algorithmic_bytes": sum(alg.values()),
+                               "achieved": round(sum(alg.values()) / (ms_per_step * 1e-3) / 1e9, 1),
+                               "frac": round(sum(alg.values()) / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
+                "segments_ms": {n: round(float(v), 5) for n, v in zip(names, seg_mean)}}
+
+    result = {
+        "metric": "visual tokens compressed/sec (OIM+SPU)", "value": round(tokens_per_s, 1), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "tokens_per_step": w.tokens_in, "oim": f"{w.grids}x{w.H}x{w.W}x{w.D}",
+                   "spu": f"{w.spu_B}x{w.spu_N}x{w.spu_D}", "n_keep": w.n_keep, "sigma": w.sigma,
+                   "rotating_input_sets": n_rot, "input_gen_s": round(gen_s, 1)},
+        "roofline": roofline,
+    }
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(w, x_oim_host, x_spu_host)
+    print(json.dumps(result))
+
+
+def cpu_baseline(w, x_oim_host, x_spu_host):
+    """The oracle as it stands, on a bounded sample of the same inputs, on this host's cores."""
+    import numpy as np
+    import oracle
+    from paper_2512_09010_amd import workloads as wl
+
+    n_s = min(w.spu_B, 4)                                   # SPU samples (each an independent OpenMP job)
+    frac = n_s / w.spu_B
+    n_g = max(1, int(round(w.grids * frac)))
+    rm = oracle.ROUND_BF16 if w.dtype == "bf16" else oracle.ROUND_F32
+    xo = wl.widen(x_oim_host[:n_g], w.dtype)
+    xs = wl.widen(x_spu_host[:n_s], w.dtype)
+    oracle.lib()
+    t0 = time.perf_counter()
+    cur, sizes = xo, None
+    for passes in w.oim_calls:
+        r = oracle.oim_merge(cur, passes, sizes=sizes, round_mode=rm)
+        cur, sizes = r["x"], r["sizes"]
+    t1 = time.perf_counter()
+    sc = oracle.spu_score(xs, w.sigma, True)
+    oracle.spu_prune(sc, w.n_keep, xs)
+    t2 = time.perf_counter()
+    tokens = n_g * w.H * w.W
+    ncpu = os.cpu_count() or 1
+    omp = int(os.environ.get("OMP_NUM_THREADS", ncpu))
+    return {"value": round(tokens / (t2 - t0), 1), "unit": "tokens/s", "cores": omp, "kind": "oracle",
+            "threads_used": {"oim": omp, "spu": int(min(omp, n_s))},
+            "sample": f"{n_g} of {w.grids} OIM grids + {n_s} of {w.spu_B} SPU samples of {w.name}",
+            "seconds": {"oim": round(t1 - t0, 3), "spu": round(t2 - t1, 3)}}
+
+
+if __name__ == "__main__":
+    main()
