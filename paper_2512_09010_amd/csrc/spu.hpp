@@ -8,13 +8,19 @@ constexpr int kSpuMaxN = 32768;     // tokens per sample (twiddle index arithmet
 
 // Offsets (bytes) of the score kernels' scratch inside the caller's workspace.
 struct SpuLayout {
-    size_t tw, gk, Fc, Fs, partial, bytes;
+    size_t tw, gk, gm, Fc, Fs, partial, bytes;
     int n_tiles;
+    bool fast;      // transform-decomposition FFT path instead of the direct pass-band DFT
 };
 SpuLayout spu_layout(int B, int N, int D, int sigma);
 
 luvc_status spu_score_dense(const void* x, int B, int N, int D, int64_t row_stride, luvc_dtype dt, int sigma,
                             int use_hamming, float* scores, void* workspace, hipStream_t st);
+
+// Fast path (spu_fft.hip): N = 256 * N2, 2 * sigma + 1 <= 256.
+bool spu_fft_supported(int N, int sigma);
+luvc_status spu_score_fft(const void* x, int B, int N, int D, int64_t row_stride, luvc_dtype dt, int sigma,
+                          const float2* tw, const float* gm, float* partial, int n_tiles, hipStream_t st);
 
 luvc_status spu_prune_run(const void* x, const float* scores, int B, int N, int D, int64_t row_stride, luvc_dtype dt,
                           int n_keep, int32_t* kept_idx, void* x_out, hipStream_t st);

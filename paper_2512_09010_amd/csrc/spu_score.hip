@@ -18,7 +18,7 @@
 namespace luvc {
 
 __global__ void __launch_bounds__(256)
-spu_tables(int N, int sigma, int use_hamming, float2* __restrict__ tw, float* __restrict__ gk)
+spu_tables(int N, int sigma, int use_hamming, float2* __restrict__ tw, float* __restrict__ gk, float* __restrict__ gm)
 {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < N) {
@@ -30,7 +30,8 @@ spu_tables(int N, int sigma, int use_hamming, float2* __restrict__ tw, float* __
         double w = 1.0;
         if (use_hamming && N > 1) w = 0.54 + 0.46 * cospi(2.0 * (double)i / (double)(N - 1));
         const double pair = (i == 0 || 2 * i == N) ? 1.0 : 2.0;
-        gk[i] = (float)(pair * w / (double)N);
+        gk[i] = (float)(pair * w / (double)N);     // +k and -k paired (real-signal form)
+        gm[i] = (float)(w / (double)N);            // per bin (complex form)
     }
 }
 
@@ -135,12 +136,15 @@ spu_finish(const float* __restrict__ partial, int N, int n_tiles, int64_t total,
 SpuLayout spu_layout(int B, int N, int D, int sigma)
 {
     SpuLayout L;
-    L.n_tiles = (D + 63) / 64;
+    L.fast = spu_fft_supported(N, sigma);
+    L.n_tiles = L.fast ? (D + 31) / 32 : (D + 63) / 64;
+    const size_t spec = L.fast ? 0 : (size_t)B * (sigma + 1) * D;   // pass-band spectra of the direct path
     size_t off = 0;
     L.tw = off;      off += align_up(sizeof(float2) * (size_t)N);
     L.gk = off;      off += align_up(sizeof(float) * (size_t)(sigma + 1));
-    L.Fc = off;      off += align_up(sizeof(float) * (size_t)B * (sigma + 1) * D);
-    L.Fs = off;      off += align_up(sizeof(float) * (size_t)B * (sigma + 1) * D);
+    L.gm = off;      off += align_up(sizeof(float) * (size_t)(sigma + 1));
+    L.Fc = off;      off += align_up(sizeof(float) * spec);
+    L.Fs = off;      off += align_up(sizeof(float) * spec);
     L.partial = off; off += align_up(sizeof(float) * (size_t)B * L.n_tiles * N);
     L.bytes = off;
     return L;
@@ -153,10 +157,18 @@ luvc_status spu_score_dense(const void* x, int B, int N, int D, int64_t row_stri
     char* ws = (char*)workspace;
     float2* tw = (float2*)(ws + L.tw);
     float* gk = (float*)(ws + L.gk);
+    float* gm = (float*)(ws + L.gm);
     float* Fc = (float*)(ws + L.Fc);
     float* Fs = (float*)(ws + L.Fs);
     float* partial = (float*)(ws + L.partial);
-    hipLaunchKernelGGL(spu_tables, dim3((unsigned)((N + 255) / 256)), dim3(256), 0, st, N, sigma, use_hamming, tw, gk);
+    hipLaunchKernelGGL(spu_tables, dim3((unsigned)((N + 255) / 256)), dim3(256), 0, st, N, sigma, use_hamming, tw, gk, gm);
+    const int64_t total = (int64_t)B * N;
+    if (L.fast) {
+        const luvc_status rc = spu_score_fft(x, B, N, D, row_stride, dt, sigma, tw, gm, partial, L.n_tiles, st);
+        if (rc != LUVC_OK) return rc;
+        hipLaunchKernelGGL(spu_finish, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, partial, N, L.n_tiles, total, scores);
+        return check_launch("spu score");
+    }
     const dim3 gf((unsigned)L.n_tiles, (unsigned)((sigma + 1 + 4 * kKPW - 1) / (4 * kKPW)), (unsigned)B);
     if (dt == LUVC_F32)
         hipLaunchKernelGGL((spu_fwd_dense<float>), gf, dim3(256), 0, st, (const float*)x, N, D, row_stride, sigma, tw, Fc, Fs);
@@ -164,7 +176,6 @@ luvc_status spu_score_dense(const void* x, int B, int N, int D, int64_t row_stri
         hipLaunchKernelGGL((spu_fwd_dense<bf16_t>), gf, dim3(256), 0, st, (const bf16_t*)x, N, D, row_stride, sigma, tw, Fc, Fs);
     const dim3 gi((unsigned)L.n_tiles, (unsigned)((N + kNChunk - 1) / kNChunk), (unsigned)B);
     hipLaunchKernelGGL(spu_inv_dense, gi, dim3(256), 0, st, Fc, Fs, N, D, sigma, tw, gk, partial);
-    const int64_t total = (int64_t)B * N;
     hipLaunchKernelGGL(spu_finish, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, partial, N, L.n_tiles, total, scores);
     return check_launch("spu score");
 }

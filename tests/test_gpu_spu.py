@@ -35,6 +35,9 @@ def score_case(oracle, x_io, dtype, sigma, ham=True, tag="", stride_pad=0):
 @pytest.mark.parametrize("B,N,D,sigma", [
     (1, 1, 8, 0), (1, 2, 8, 1), (2, 5, 3, 2), (2, 16, 64, 3), (1, 97, 70, 10), (2, 144, 200, 18),
     (1, 196, 130, 4), (1, 256, 64, 128), (2, 130, 65, 0), (1, 300, 96, 31),
+    # shapes served by the transform-decomposition FFT path (N = 256 * N2, 2 sigma + 1 <= 256)
+    (2, 256, 64, 20), (1, 256, 32, 127), (1, 512, 70, 127), (1, 768, 33, 50), (2, 1024, 96, 102), (1, 2048, 40, 0),
+    (1, 1280, 31, 64),
 ])
 def test_score_small_random(oracle, dtype, B, N, D, sigma):
     rng = np.random.default_rng(N * 31 + D)
@@ -47,6 +50,11 @@ def test_score_strided_rows(oracle):
     rng = np.random.default_rng(3)
     x = wl.cast_io(rng.standard_normal((2, 40, 72)).astype(np.float32), "bf16")
     score_case(oracle, x, "bf16", 5, True, "strided", stride_pad=24)
+    x = wl.cast_io(rng.standard_normal((2, 512, 72)).astype(np.float32), "bf16")
+    score_case(oracle, x, "bf16", 30, True, "strided-fft", stride_pad=24)
+    score_case(oracle, x, "bf16", 30, True, "strided-fft-odd", stride_pad=7)       # odd token stride: unaligned pairs
+    xf = rng.standard_normal((1, 256, 50)).astype(np.float32)
+    score_case(oracle, xf, "f32", 9, False, "strided-fft-f32", stride_pad=3)
 
 
 def test_score_special_signals(oracle):
