@@ -199,8 +199,11 @@ luvc_status luvc_oim_merge(const void* x, const int32_t* sizes_in, int B, int H,
         int32_t* pm = (int32_t*)(ws + L.maps[i]);
         maps[i] = pm;
         n_in[i] = pl.h[i] * pl.w[i];
-        const luvc_status rc = oim_general_pass(cur_x, cur_s, B, pl.h[i], pl.w[i], D, dtype, passes[i].axis, passes[i].m, vec,
-                                                ox, os, pm, cur_k, ok, sc, st);
+        const luvc_status rc =
+            oim_halve_supported(pl.h[i], pl.w[i], D, dtype, passes[i].axis, passes[i].m, vec)
+                ? oim_halve_pass(cur_x, cur_s, B, pl.h[i], pl.w[i], D, dtype, passes[i].axis, ox, os, pm, cur_k, ok, st)
+                : oim_general_pass(cur_x, cur_s, B, pl.h[i], pl.w[i], D, dtype, passes[i].axis, passes[i].m, vec,
+                                   ox, os, pm, cur_k, ok, sc, st);
         if (rc != LUVC_OK) return rc;
         cur_x = ox;
         cur_s = os;

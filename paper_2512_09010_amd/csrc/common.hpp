@@ -30,19 +30,23 @@ __device__ __forceinline__ uint16_t f32_to_bf16(float f)
     return (uint16_t)(u >> 16);
 }
 
-// fp64 -> bf16 with a single rounding (round-to-odd into fp32 first, then nearest-even):
-// a value computed in fp64 lands on the same bf16 as the exact result would.
+// fp64 -> bf16 with a single rounding.  Rounding to fp32 first and then to bf16 differs from the
+// direct rounding only when the fp32 value lands exactly on a bf16 midpoint although v was not on
+// it; then the fp32 value is nudged one step back toward v before the nearest-even rounding.
+// Branch-free.
 __device__ __forceinline__ uint16_t f64_to_bf16(double v)
 {
-    float f = (float)v;                                   // nearest-even
-    if (isfinite(f) && (double)f != v) {                  // inexact: force the sticky (odd) bit
-        uint32_t u = __float_as_uint(f);
-        const bool away = fabs((double)f) > fabs(v);      // f was rounded away from zero
-        if (away) u -= 1;                                 // truncate toward zero ...
-        u |= 1u;                                          // ... and mark inexact
-        f = __uint_as_float(u);
-    }
-    return f32_to_bf16(f);
+    const float f = (float)v;                             // nearest-even
+    uint32_t u = __float_as_uint(f);
+    const double back = (double)f;
+    const bool mid = (u & 0xffffu) == 0x8000u;
+    const bool finite = (u & 0x7f800000u) != 0x7f800000u;
+    // |f| > |v|: f was rounded away from zero, step the magnitude down; |f| < |v|: step it up
+    const int adj = (fabs(back) > fabs(v)) ? -1 : ((fabs(back) < fabs(v)) ? 1 : 0);
+    u += (mid && finite) ? (uint32_t)adj : 0u;
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);   // NaN stays NaN
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
 }
 
 template <typename T> struct io_traits;

@@ -20,6 +20,12 @@ luvc_status oim_general_pass(const void* x, const int32_t* sizes_in, int B, int 
                              const int32_t* kept_prev, int32_t* kept_out,
                              const OimScratch& ws, hipStream_t st);
 
+// Fused pass for m = ceil(len/2) (oim_fast.hip); `vec` = rows are 16-byte aligned.
+bool oim_halve_supported(int H, int W, int D, luvc_dtype dt, int axis, int m, bool vec);
+luvc_status oim_halve_pass(const void* x, const int32_t* sizes_in, int B, int H, int W, int D, luvc_dtype dt, int axis,
+                           void* x_out, int32_t* sizes_out, int32_t* pass_map, const int32_t* kept_prev, int32_t* kept_out,
+                           hipStream_t st);
+
 luvc_status oim_compose(const int32_t* const* maps, const int32_t* n_in, int n, int B, int n_first,
                         int32_t* merged_out, hipStream_t st);
 

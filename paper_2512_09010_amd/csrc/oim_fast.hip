@@ -1,0 +1,321 @@
+// OIM (paper Section 3.2) - fused single-launch pass for the schedules that merge EVERY source
+// of a line (m = ceil(len/2), the halving used by the benchmark configurations).
+//
+// With every source merged the survivors are exactly the destinations (odd positions), so output
+// slot j of a line is destination 2j+1 and no per-line ranking is needed.  One wavefront produces
+// one output token: it keeps source a = 2j, destination b = 2j+1 and the next source c = 2j+2 in
+// registers (each token is read once per use, 16 bytes per lane per access), accumulates the
+// squared norms and the two neighbour dot products in fp64, trades those four scalars with the
+// neighbouring wavefronts of its workgroup through LDS, decides where a and c go, and writes the
+// size-weighted mean.  The waves at the two ends of a workgroup's run of slots evaluate the one
+// or two halo tokens they need themselves, with the same routine, so the decision about a source
+// is bit-identical in both wavefronts that look at it.
+#include <cstdlib>
+
+#include "common.hpp"
+#include "oim.hpp"
+
+namespace luvc {
+
+namespace {
+
+struct Scal { double na, nb, dab, dbc; };     // |a|^2, |b|^2, a.b, b.c of one slot
+
+template <typename T, int NCH>
+struct Tok {
+    typename io_traits<T>::vec_t v[NCH];
+};
+
+typedef unsigned int u32x4 __attribute__((__vector_size__(16)));
+
+// One token = one buffer resource: lanes past the end of the token read zeros from the hardware
+// bounds check, so the 16-byte loads need no branch and all of them can be in flight together.
+template <typename T, int NCH>
+__device__ __forceinline__ void load_tok(Tok<T, NCH>& t, const T* p, int D, int lane, bool present = true)
+{
+    using tr = io_traits<T>;
+    constexpr int V = tr::kVec;
+    // a token that is not there (past the end of the line) is a zero-length buffer: every lane reads zeros
+    const __amdgpu_buffer_rsrc_t rsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<T*>(p), 0, present ? D * (int)sizeof(T) : 0, 0x00020000);
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+        const u32x4 r = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (i * 64 + lane) * V * (int)sizeof(T), 0, 0);
+        typename tr::vec_t v;
+        __builtin_memcpy(&v, &r, 16);
+        t.v[i] = v;
+    }
+}
+
+// element e (compile-time) of a 16-byte chunk as fp32
+template <typename T> __device__ __forceinline__ float elem(const typename io_traits<T>::vec_t& v, int e);
+template <> __device__ __forceinline__ float elem<float>(const float4& v, int e)
+{
+    return e == 0 ? v.x : e == 1 ? v.y : e == 2 ? v.z : v.w;
+}
+template <> __device__ __forceinline__ float elem<bf16_t>(const uint4& v, int e)
+{
+    const uint32_t wd = (e >> 1) == 0 ? v.x : (e >> 1) == 1 ? v.y : (e >> 1) == 2 ? v.z : v.w;
+    return __uint_as_float((e & 1) ? (wd & 0xffff0000u) : (wd << 16));
+}
+
+// Similarity sweep of one wavefront.  Always: |a|^2, |b|^2, a.b, b.c.  With HALO: also |c|^2, |h|^2 and
+// h.a (LEFT: h is the token before a) or c.h (h is the token after c).
+template <typename T, int NCH, bool HALO, bool LEFT>
+__device__ __forceinline__ void sweep(const Tok<T, NCH>& A, const Tok<T, NCH>& B, const Tok<T, NCH>& C, const Tok<T, NCH>& Hx,
+                                      Scal& me, double& ncc, double& nhh, double& dh)
+{
+    constexpr int V = io_traits<T>::kVec;
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+#pragma unroll
+        for (int e = 0; e < V; ++e) {
+            const double a = (double)elem<T>(A.v[i], e), b = (double)elem<T>(B.v[i], e), c = (double)elem<T>(C.v[i], e);
+            me.na = fma(a, a, me.na);
+            me.nb = fma(b, b, me.nb);
+            me.dab = fma(a, b, me.dab);
+            me.dbc = fma(b, c, me.dbc);
+            if (HALO) {
+                const double h = (double)elem<T>(Hx.v[i], e);
+                ncc = fma(c, c, ncc);
+                nhh = fma(h, h, nhh);
+                dh = LEFT ? fma(h, a, dh) : fma(c, h, dh);
+            }
+        }
+    }
+}
+
+// Hides a token's registers from value numbering: the merge phase re-widens the packed data instead
+// of keeping the fp64 copies of the similarity phase alive across the barrier (which spills).
+template <typename T, int NCH>
+__device__ __forceinline__ void forget(Tok<T, NCH>& t)
+{
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+        uint32_t* q = reinterpret_cast<uint32_t*>(&t.v[i]);
+        asm volatile("" : "+v"(q[0]), "+v"(q[1]), "+v"(q[2]), "+v"(q[3]));
+    }
+}
+
+__device__ __forceinline__ double clamp_norm(double n2)
+{
+    const double n = sqrt(n2);
+    return n < 1e-12 ? 1e-12 : n;
+}
+
+// Does the source (squared norm ns) go to its LEFT destination?  tie -> left (lower position)
+__device__ __forceinline__ bool source_goes_left(bool has_left, bool has_right, double ns,
+                                                 double dot_l, double nl, double dot_r, double nr)
+{
+    if (!has_left) return false;
+    if (!has_right) return true;
+    const double n = clamp_norm(ns);
+    const double sl = dot_l / (n * clamp_norm(nl));
+    const double sr = dot_r / (n * clamp_norm(nr));
+    return !(sr > sl);
+}
+
+}  // namespace
+
+template <typename T, int NCH>
+__global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(NCH <= 3 ? 4 : 2)))
+oim_halve(const T* __restrict__ x, const int32_t* __restrict__ sizes_in, int H, int W, int D, int axis,
+          int tiles_per_line, int slots_per_tile,
+          const int32_t* __restrict__ kept_prev, T* __restrict__ x_out, int32_t* __restrict__ sizes_out,
+          int32_t* __restrict__ pass_map, int32_t* __restrict__ kept_out)
+{
+    using tr = io_traits<T>;
+    constexpr int V = tr::kVec;
+    __shared__ Scal sc[8];
+    __shared__ double halo[5];                    // left: |l|^2, l.a0 ; right: |c|^2, |r|^2, c.r
+
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int len = axis ? W : H, nlines = axis ? H : W;
+    const int nd = len >> 1;                      // destinations = output slots per line
+    const int Wo = axis ? nd : W;
+    const int tile = blockIdx.x % tiles_per_line;
+    const int line = (blockIdx.x / tiles_per_line) % nlines;
+    const int b = blockIdx.x / (tiles_per_line * nlines);
+    const int j0 = tile * slots_per_tile;
+    const int nslot = min(slots_per_tile, nd - j0);        // live waves of this workgroup
+    const int j = j0 + w;
+    const bool live = w < nslot;
+    const int64_t step = axis ? 1 : W;                     // tokens between neighbours on the line
+    const int64_t img = (int64_t)b * H * W;
+    const int64_t line0 = img + (axis ? (int64_t)line * W : line);    // token index of position 0
+    auto tok_ptr = [&](int pos) { return x + (line0 + pos * step) * D; };
+
+    Tok<T, NCH> A, Bt, C;
+    const int pa = 2 * j, pb = 2 * j + 1, pc = 2 * j + 2;
+    const bool has_c = live && pc < len;
+    Scal me{0, 0, 0, 0};
+    if (live) {
+        // the end waves of the workgroup also need one token beyond its run of slots
+        const bool need_l = (w == 0) && pa >= 1;
+        const bool need_r = (w == nslot - 1) && has_c;     // c's own right neighbour, if any, decides with us
+        const bool has_r = need_r && pc + 1 < len;
+        Tok<T, NCH> Hx;
+        load_tok<T, NCH>(A, tok_ptr(pa), D, lane);
+        load_tok<T, NCH>(Bt, tok_ptr(pb), D, lane);
+        load_tok<T, NCH>(C, tok_ptr(has_c ? pc : pb), D, lane, has_c);
+        load_tok<T, NCH>(Hx, tok_ptr(need_l ? pa - 1 : (has_r ? pc + 1 : pb)), D, lane, need_l || has_r);
+        double nl = 0.0, dl = 0.0, nc = 0.0, nr = 0.0, dcr = 0.0;
+        // every accumulator sees its terms in the same (chunk, element) order in whichever wavefront
+        // evaluates it, so a dot product shared by two wavefronts has the same bits in both
+        if (need_l) {
+            sweep<T, NCH, true, true>(A, Bt, C, Hx, me, nc, nl, dl);
+            if (has_r) {                                    // single-wave workgroup: the other end as well
+                load_tok<T, NCH>(Hx, tok_ptr(pc + 1), D, lane);
+                double unused = 0.0;
+                Scal tmp{0, 0, 0, 0};
+                sweep<T, NCH, true, false>(A, Bt, C, Hx, tmp, unused, nr, dcr);
+            }
+        } else if (need_r) {
+            sweep<T, NCH, true, false>(A, Bt, C, Hx, me, nc, nr, dcr);
+        } else {
+            double u0 = 0.0, u1 = 0.0, u2 = 0.0;
+            sweep<T, NCH, false, false>(A, Bt, C, Hx, me, u0, u1, u2);
+        }
+        me.na = wave_sum(me.na); me.nb = wave_sum(me.nb); me.dab = wave_sum(me.dab);
+        if (has_c) me.dbc = wave_sum(me.dbc);
+        if (need_l) {
+            nl = wave_sum(nl); dl = wave_sum(dl);
+            if (lane == 0) { halo[0] = nl; halo[1] = dl; }
+        }
+        if (need_r) {
+            nc = wave_sum(nc);
+            if (has_r) { nr = wave_sum(nr); dcr = wave_sum(dcr); }
+            if (lane == 0) { halo[2] = nc; halo[3] = nr; halo[4] = dcr; }
+        }
+        if (lane == 0) sc[w] = me;
+    }
+    __syncthreads();
+    if (!live) return;
+    forget<T, NCH>(A);
+    forget<T, NCH>(Bt);
+    forget<T, NCH>(C);
+
+    // ---- source a = 2j: right (into b) unless its left destination 2j-1 is at least as similar
+    double l_nb = 0.0, l_dbc = 0.0;               // |2j-1|^2 and <2j-1, 2j>
+    if (pa >= 1) {
+        if (w > 0) { l_nb = sc[w - 1].nb; l_dbc = sc[w - 1].dbc; }
+        else { l_nb = halo[0]; l_dbc = halo[1]; }
+    }
+    const bool a_left = source_goes_left(pa >= 1, true, me.na, l_dbc, l_nb, me.dab, me.nb);
+    // ---- source c = 2j+2: left (into b) unless its right destination 2j+3 is strictly more similar
+    bool c_left = false;
+    if (has_c) {
+        double nc, nr, dcr;
+        if (w + 1 < nslot) { nc = sc[w + 1].na; nr = sc[w + 1].nb; dcr = sc[w + 1].dab; }
+        else { nc = halo[2]; nr = halo[3]; dcr = halo[4]; }
+        c_left = source_goes_left(true, pc + 1 < len, nc, me.dbc, me.nb, dcr, nr);
+    }
+    const bool take_a = !a_left, take_c = c_left;
+
+    const int64_t ta = line0 + pa * step, tb = line0 + pb * step, tc = line0 + pc * step;
+    const int sb = sizes_in ? sizes_in[tb] : 1;
+    const int sa = take_a ? (sizes_in ? sizes_in[ta] : 1) : 0;
+    const int scz = take_c ? (sizes_in ? sizes_in[tc] : 1) : 0;
+    const int S = sb + sa + scz;
+    const int64_t n_out_per = (int64_t)(axis ? H : nd) * Wo;
+    const int out_in_img = axis ? line * Wo + j : j * Wo + line;
+    const int64_t slot = b * n_out_per + out_in_img;
+    if (lane == 0) {
+        sizes_out[slot] = S;
+        const int p_in = (int)(tb - img);
+        if (kept_out) kept_out[slot] = kept_prev ? kept_prev[img + p_in] : p_in;
+        // a lands here or in the previous slot of the line; the last source of an odd line has no
+        // slot of its own and always folds into the last destination
+        const int prev_slot = axis ? out_in_img - 1 : out_in_img - Wo;
+        pass_map[tb] = out_in_img;
+        pass_map[ta] = take_a ? out_in_img : prev_slot;
+        if (has_c && pc + 1 >= len) pass_map[tc] = out_in_img;
+    }
+    T* o = x_out + slot * D;
+    if (!take_a && !take_c) {                     // nothing absorbed: bit copy
+#pragma unroll
+        for (int i = 0; i < NCH; ++i) {
+            const int d = (i * 64 + lane) * V;
+            if (d < D) *reinterpret_cast<typename tr::vec_t*>(o + d) = Bt.v[i];
+        }
+        return;
+    }
+    // size-weighted mean in fp64, terms in position order b, a, c (sizes of absent terms are 0).  The
+    // quotient is formed with the reciprocal and one residual correction: exact whenever acc / S is
+    // representable, which covers every rounding boundary of the storage types.
+    const double dsb = sb, dsa = sa, dsc = scz, dS = S, rS = 1.0 / dS;
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+        const int d = (i * 64 + lane) * V;
+        T r[V];
+#pragma unroll
+        for (int e = 0; e < V; ++e) {
+            double acc = dsb * (double)elem<T>(Bt.v[i], e);
+            acc = fma(dsa, (double)elem<T>(A.v[i], e), acc);
+            acc = fma(dsc, (double)elem<T>(C.v[i], e), acc);
+            double q = acc * rS;
+            q = fma(fma(-q, dS, acc), rS, q);
+            tr::store(&r[e], q);
+        }
+        if (d < D) *reinterpret_cast<typename tr::vec_t*>(o + d) = *reinterpret_cast<const typename tr::vec_t*>(r);
+    }
+}
+
+template <typename T, int NCH>
+static void launch_halve(const T* x, const int32_t* sizes_in, int B, int H, int W, int D, int axis,
+                         const int32_t* kept_prev, T* x_out, int32_t* sizes_out, int32_t* pass_map, int32_t* kept_out,
+                         hipStream_t st)
+{
+    const int len = axis ? W : H, nlines = axis ? H : W, nd = len / 2;
+    static const int tune = getenv("LUVC_OIM_SPT") ? atoi(getenv("LUVC_OIM_SPT")) : 4;   // tuning knob, 1..8
+    const int cap = tune < 1 ? 1 : (tune > 8 ? 8 : tune);
+    const int spt = nd < cap ? nd : cap;                   // wavefronts (= output slots) per workgroup
+    const int tiles = (nd + spt - 1) / spt;
+    hipLaunchKernelGGL((oim_halve<T, NCH>), dim3((unsigned)((int64_t)B * nlines * tiles)), dim3(64 * spt), 0, st,
+                       x, sizes_in, H, W, D, axis, tiles, spt, kept_prev, x_out, sizes_out, pass_map, kept_out);
+}
+
+template <typename T>
+static bool dispatch_halve(const T* x, const int32_t* sizes_in, int B, int H, int W, int D, int axis,
+                           const int32_t* kept_prev, T* x_out, int32_t* sizes_out, int32_t* pass_map, int32_t* kept_out,
+                           hipStream_t st)
+{
+    const int per_wave = 64 * io_traits<T>::kVec;
+    const int nch = (D + per_wave - 1) / per_wave;
+#define LUVC_HALVE(N) launch_halve<T, N>(x, sizes_in, B, H, W, D, axis, kept_prev, x_out, sizes_out, pass_map, kept_out, st); return true
+    switch (nch) {
+        case 1: LUVC_HALVE(1);
+        case 2: LUVC_HALVE(2);
+        case 3: LUVC_HALVE(3);
+        case 4: LUVC_HALVE(4);
+        case 5: LUVC_HALVE(5);
+        case 6: LUVC_HALVE(6);
+        case 7: LUVC_HALVE(7);
+        case 8: LUVC_HALVE(8);
+        default: return false;
+    }
+#undef LUVC_HALVE
+}
+
+bool oim_halve_supported(int H, int W, int D, luvc_dtype dt, int axis, int m, bool vec)
+{
+    const int len = axis ? W : H;
+    const int per_wave = 64 * (dt == LUVC_F32 ? 4 : 8);
+    return vec && len >= 2 && m == (len + 1) / 2 && (D + per_wave - 1) / per_wave <= 8;
+}
+
+luvc_status oim_halve_pass(const void* x, const int32_t* sizes_in, int B, int H, int W, int D, luvc_dtype dt, int axis,
+                           void* x_out, int32_t* sizes_out, int32_t* pass_map, const int32_t* kept_prev, int32_t* kept_out,
+                           hipStream_t st)
+{
+    bool ok;
+    if (dt == LUVC_F32)
+        ok = dispatch_halve<float>((const float*)x, sizes_in, B, H, W, D, axis, kept_prev, (float*)x_out, sizes_out, pass_map, kept_out, st);
+    else
+        ok = dispatch_halve<bf16_t>((const bf16_t*)x, sizes_in, B, H, W, D, axis, kept_prev, (bf16_t*)x_out, sizes_out, pass_map, kept_out, st);
+    if (!ok) { set_error("oim_halve_pass: unsupported D"); return LUVC_ERR_UNSUPPORTED; }
+    return check_launch("oim halving pass");
+}
+
+}  // namespace luvc

@@ -45,6 +45,8 @@ __device__ __forceinline__ int block_scan_incl(int v, int* wave_tot /*[16]*/, in
     return s + base;
 }
 
+constexpr int kSelMaxRegKeys = 8;                     // keys cached in registers per thread (N <= 8 * 1024)
+
 __global__ void __launch_bounds__(kSelThreads)
 spu_select(const float* __restrict__ scores, int N, int n_keep, int32_t* __restrict__ kept_idx)
 {
@@ -56,41 +58,58 @@ spu_select(const float* __restrict__ scores, int N, int n_keep, int32_t* __restr
     const float* s = scores + (int64_t)b * N;
     int32_t* out = kept_idx + (int64_t)b * n_keep;
 
+    // keys of tokens tid, tid + 1024, ... stay in registers when the sample is small enough
+    const bool cached = N <= kSelMaxRegKeys * kSelThreads;
+    uint32_t key[kSelMaxRegKeys];
+#pragma unroll
+    for (int i = 0; i < kSelMaxRegKeys; ++i) {
+        const int n = tid + i * kSelThreads;
+        key[i] = (cached && n < N) ? score_key(s[n]) : 0u;
+    }
+
     uint32_t prefix = 0, mask = 0;
     int remaining = n_keep;                            // still to pick among keys matching the prefix
     for (int shift = 24; shift >= 0; shift -= 8) {
         if (tid < 256) hist[tid] = 0;
         __syncthreads();
-        for (int n = tid; n < N; n += blockDim.x) {
-            const uint32_t k = score_key(s[n]);
-            if ((k & mask) == prefix) atomicAdd(&hist[(k >> shift) & 255u], 1);
+        if (cached) {
+#pragma unroll
+            for (int i = 0; i < kSelMaxRegKeys; ++i)
+                if (tid + i * kSelThreads < N && (key[i] & mask) == prefix) atomicAdd(&hist[(key[i] >> shift) & 255u], 1);
+        } else {
+            for (int n = tid; n < N; n += kSelThreads) {
+                const uint32_t k = score_key(s[n]);
+                if ((k & mask) == prefix) atomicAdd(&hist[(k >> shift) & 255u], 1);
+            }
         }
         __syncthreads();
-        if (tid == 0) {
-            int above = 0, bin = 255;
-            for (; bin > 0; --bin) {                   // largest digit first
-                const int h = hist[bin];
-                if (above + h >= remaining) break;
-                above += h;
-            }
-            sh_prefix = prefix | ((uint32_t)bin << shift);
-            sh_remaining = remaining - above;
+        // digit d is the one where (tokens with a larger digit) < remaining <= (those plus hist[d]);
+        // thread i looks at digit 255 - i so that an inclusive scan counts "this digit and larger"
+        int h = 0, incl = 0, tot;
+        if (tid < 256) h = hist[255 - tid];
+        incl = block_scan_incl(tid < 256 ? h : 0, wave_tot, &tot);
+        if (tid < 256 && incl - h < remaining && remaining <= incl) {
+            sh_prefix = prefix | ((uint32_t)(255 - tid) << shift);
+            sh_remaining = remaining - (incl - h);
         }
         __syncthreads();
         prefix = sh_prefix;
         remaining = sh_remaining;
         mask |= 255u << shift;
-        __syncthreads();
     }
     const uint32_t T = prefix;                         // key of the n_keep-th largest score
     const int take_eq = remaining;                     // tokens with key == T that are kept (lowest indices)
 
     int eq_before = 0, sel_before = 0;
-    for (int n0 = 0; n0 < N; n0 += blockDim.x) {
+    for (int n0 = 0, i = 0; n0 < N; n0 += kSelThreads, ++i) {
         const int n = n0 + tid;
         uint32_t k = 0;
         bool eq = false, gt = false;
-        if (n < N) { k = score_key(s[n]); eq = (k == T); gt = (k > T); }
+        if (n < N) {
+            k = score_key(s[n]);                       // L1/L2-resident re-read; keeps the loop free of dynamic register indexing
+            eq = (k == T);
+            gt = (k > T);
+        }
         int tot_eq, tot_sel;
         const int eq_incl = block_scan_incl(eq ? 1 : 0, wave_tot, &tot_eq);
         const bool sel = gt || (eq && (eq_before + eq_incl - 1) < take_eq);

@@ -120,16 +120,29 @@ spu_inv_dense(const float* __restrict__ Fc, const float* __restrict__ Fs, int N,
     }
 }
 
-__global__ void __launch_bounds__(256)
+// Eq. 8: fixed-order sum of the per-tile energies, then the square root.  A workgroup owns 64
+// consecutive tokens; its 8 waves split the channel tiles, partial sums meet in LDS in wave order.
+constexpr int kFinParts = 8;
+__global__ void __launch_bounds__(64 * kFinParts)
 spu_finish(const float* __restrict__ partial, int N, int n_tiles, int64_t total, float* __restrict__ scores)
 {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= total) return;
-    const int64_t b = i / N;
-    const int n = (int)(i - b * N);
+    __shared__ double part_sum[kFinParts][64];
+    const int lane = threadIdx.x & 63, part = threadIdx.x >> 6;
+    const int64_t i = (int64_t)blockIdx.x * 64 + lane;
     double e = 0.0;
-    for (int t = 0; t < n_tiles; ++t) e += (double)partial[(b * n_tiles + t) * N + n];
-    scores[i] = (float)sqrt(e);
+    if (i < total) {
+        const int64_t b = i / N;
+        const int n = (int)(i - b * N);
+        for (int t = part; t < n_tiles; t += kFinParts) e += (double)partial[(b * n_tiles + t) * N + n];
+    }
+    part_sum[part][lane] = e;
+    __syncthreads();
+    if (part == 0 && i < total) {
+        double tot = 0.0;
+#pragma unroll
+        for (int p = 0; p < kFinParts; ++p) tot += part_sum[p][lane];
+        scores[i] = (float)sqrt(tot);
+    }
 }
 
 // ------------------------------------------------------------------ host side
@@ -166,7 +179,7 @@ luvc_status spu_score_dense(const void* x, int B, int N, int D, int64_t row_stri
     if (L.fast) {
         const luvc_status rc = spu_score_fft(x, B, N, D, row_stride, dt, sigma, tw, gm, partial, L.n_tiles, st);
         if (rc != LUVC_OK) return rc;
-        hipLaunchKernelGGL(spu_finish, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, partial, N, L.n_tiles, total, scores);
+        hipLaunchKernelGGL(spu_finish, dim3((unsigned)((total + 63) / 64)), dim3(64 * kFinParts), 0, st, partial, N, L.n_tiles, total, scores);
         return check_launch("spu score");
     }
     const dim3 gf((unsigned)L.n_tiles, (unsigned)((sigma + 1 + 4 * kKPW - 1) / (4 * kKPW)), (unsigned)B);
@@ -176,7 +189,7 @@ luvc_status spu_score_dense(const void* x, int B, int N, int D, int64_t row_stri
         hipLaunchKernelGGL((spu_fwd_dense<bf16_t>), gf, dim3(256), 0, st, (const bf16_t*)x, N, D, row_stride, sigma, tw, Fc, Fs);
     const dim3 gi((unsigned)L.n_tiles, (unsigned)((N + kNChunk - 1) / kNChunk), (unsigned)B);
     hipLaunchKernelGGL(spu_inv_dense, gi, dim3(256), 0, st, Fc, Fs, N, D, sigma, tw, gk, partial);
-    hipLaunchKernelGGL(spu_finish, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, partial, N, L.n_tiles, total, scores);
+    hipLaunchKernelGGL(spu_finish, dim3((unsigned)((total + 63) / 64)), dim3(64 * kFinParts), 0, st, partial, N, L.n_tiles, total, scores);
     return check_launch("spu score");
 }
 
