@@ -60,75 +60,103 @@ __device__ __forceinline__ void fft16(cf (&v)[16])
         for (int p = q + 1; p < 4; ++p) { const cf s = v[4 * q + p]; v[4 * q + p] = v[4 * p + q]; v[4 * p + q] = s; }
 }
 
+typedef unsigned int u32x2 __attribute__((__vector_size__(8)));
+
+// One channel pair of one token.  Rows are addressed through a buffer resource that spans the whole
+// sample; a lane whose pair lies past D is given an offset beyond the resource and reads zeros, so
+// the loads need no branch.
 template <typename T> struct pair_io;
 template <> struct pair_io<bf16_t> {
     using raw_t = uint32_t;
-    __device__ static __forceinline__ raw_t load(const bf16_t* p, bool second, bool aligned)
+    __device__ static __forceinline__ raw_t load(__amdgpu_buffer_rsrc_t r, uint32_t off, bool second, bool aligned)
     {
-        if (aligned) return *reinterpret_cast<const uint32_t*>(p);
-        const uint32_t lo = p[0].bits, hi = second ? p[1].bits : 0u;
-        return lo | (hi << 16);
+        if (aligned) return __builtin_amdgcn_raw_buffer_load_b32(r, off, 0, 0);
+        const uint32_t lo = __builtin_amdgcn_raw_buffer_load_b16(r, off, 0, 0);
+        const uint32_t hi = second ? (uint32_t)__builtin_amdgcn_raw_buffer_load_b16(r, off + 2, 0, 0) : 0u;
+        return (lo & 0xffffu) | (hi << 16);
     }
     __device__ static __forceinline__ cf widen(raw_t r) { return {__uint_as_float(r << 16), __uint_as_float(r & 0xffff0000u)}; }
-    __device__ static __forceinline__ raw_t zero() { return 0u; }
 };
 template <> struct pair_io<float> {
-    using raw_t = float2;
-    __device__ static __forceinline__ raw_t load(const float* p, bool second, bool aligned)
+    using raw_t = u32x2;
+    __device__ static __forceinline__ raw_t load(__amdgpu_buffer_rsrc_t r, uint32_t off, bool second, bool aligned)
     {
-        if (aligned) return *reinterpret_cast<const float2*>(p);
-        return make_float2(p[0], second ? p[1] : 0.f);
+        if (aligned) return __builtin_amdgcn_raw_buffer_load_b64(r, off, 0, 0);
+        raw_t v;
+        v[0] = __builtin_amdgcn_raw_buffer_load_b32(r, off, 0, 0);
+        v[1] = second ? __builtin_amdgcn_raw_buffer_load_b32(r, off + 4, 0, 0) : 0u;
+        return v;
     }
-    __device__ static __forceinline__ cf widen(raw_t r) { return {r.x, r.y}; }
-    __device__ static __forceinline__ raw_t zero() { return make_float2(0.f, 0.f); }
+    __device__ static __forceinline__ cf widen(raw_t r) { return {__uint_as_float(r[0]), __uint_as_float(r[1])}; }
 };
 
 constexpr int kPairs = 16;                       // channel pairs per workgroup
 constexpr int kRowPad = 16 * kPairs + kPairs;    // float2 per exchange row: 16 x 16 pairs + one pad group
 
+// sum over the 16 lanes of a DPP row; every lane of the row ends up with the total, fixed order
+__device__ __forceinline__ float row16_sum(float v)
+{
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xf, 0xf, false));    // quad_perm [1,0,3,2]
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x4E, 0xf, 0xf, false));    // quad_perm [2,3,0,1]
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x141, 0xf, 0xf, false));   // row_half_mirror
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x140, 0xf, 0xf, false));   // row_mirror
+    return v;
+}
+
 }  // namespace
 
-template <typename T>
+template <typename T, bool POW2, bool ALIGNED>
 __global__ void __launch_bounds__(256)
-spu_fft256(const T* __restrict__ x, int N, int D, int64_t row_stride, int sigma, int aligned,
+spu_fft256(const T* __restrict__ x, int N, int D, int64_t row_stride, int sigma,
            const float2* __restrict__ tw_g, const float* __restrict__ gm /* M[f]/N */,
            float* __restrict__ partial /* [B, n_tiles, N] */)
 {
     using pio = pair_io<T>;
     extern __shared__ float2 smem[];
-    float2* xbuf = smem;                         // [16][kRowPad]
-    float2* tw = smem + 16 * kRowPad;            // [N]   (cos, sin)(2 pi i / N)
+    float2* xbuf = smem;                         // [16][kRowPad]  exchange between the two radix-16 passes
+    float2* tw = smem + 16 * kRowPad;            // [N]    (cos, sin)(2 pi i / N)
+    float2* tw256 = tw + N;                      // [256]  (cos, sin)(2 pi i / 256)
+    float* eperm = reinterpret_cast<float*>(tw256 + 256);   // [N2][16 t][16 j] energies of this tile
     const int tid = threadIdx.x, c = tid & 15, t = tid >> 4;
     const int tile = blockIdx.x, n_tiles = gridDim.x, b = blockIdx.y;
     const int N2 = N >> 8;
     for (int i = tid; i < N; i += 256) tw[i] = tw_g[i];
+    tw256[tid] = tw_g[tid * N2];
 
     const int d0 = tile * 32 + 2 * c;
     const bool live = d0 < D, second = d0 + 1 < D;
-    const T* xb = x + (int64_t)b * N * row_stride + (live ? d0 : 0);
+    const uint32_t es = (uint32_t)sizeof(T);
+    const uint32_t row_bytes = (uint32_t)row_stride * es;
+    // resource over sample b (N rows); lanes without a channel pair point past its end
+    const uint64_t span = (uint64_t)(N - 1) * row_bytes + (uint64_t)D * es;
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<T*>(x) + (int64_t)b * N * row_stride, 0, (int)(span > 0x7fffffffull ? 0x7fffffffull : span), 0x00020000);
+    const uint32_t lane_off = live ? (uint32_t)d0 * es : 0x80000000u;
 
     // this thread's output bins of every 256-point transform: k1 = t + 16 kb (t doubles as ka)
-    unsigned inband = 0;
     int kpos[16], ph[16];
     cf F[16];
 #pragma unroll
     for (int kb = 0; kb < 16; ++kb) {
         const int k1 = t + 16 * kb;
-        const bool lo = k1 <= sigma, hi = k1 >= 256 - sigma;
-        if (lo || hi) inband |= 1u << kb;
-        kpos[kb] = lo ? k1 : (hi ? N - 256 + k1 : 0);     // k mod N
+        kpos[kb] = k1 <= sigma ? k1 : N - 256 + k1;       // k mod N (bins outside the band are masked later)
         ph[kb] = 0;                                        // (k * n2) mod N
         F[kb] = {0.f, 0.f};
     }
+    auto advance = [&](int kb) {
+        ph[kb] += kpos[kb];
+        if (POW2) ph[kb] &= N - 1;
+        else if (ph[kb] >= N) ph[kb] -= N;
+    };
 
     typename pio::raw_t raw[16];
     auto load_sub = [&](int n2) {
 #pragma unroll
         for (int j = 0; j < 16; ++j)
-            raw[j] = live ? pio::load(xb + (int64_t)(N2 * (16 * j + t) + n2) * row_stride, second, aligned != 0) : pio::zero();
+            raw[j] = pio::load(rsrc, lane_off + (uint32_t)(N2 * (16 * j + t) + n2) * row_bytes, second, ALIGNED);
     };
     load_sub(0);
-    __syncthreads();                             // twiddle table ready
+    __syncthreads();                             // twiddle tables ready
 
     // ------------------------------------------------------------------ forward (Eq. 4 on the pass band)
     for (int n2 = 0; n2 < N2; ++n2) {
@@ -137,10 +165,12 @@ spu_fft256(const T* __restrict__ x, int N, int D, int64_t row_stride, int sigma,
         for (int j = 0; j < 16; ++j) v[j] = pio::widen(raw[j]);
         if (n2 + 1 < N2) load_sub(n2 + 1);       // next subsequence in flight while this one is transformed
         fft16<false>(v);                         // over j -> ka
+        int e256 = 0;
 #pragma unroll
         for (int ka = 0; ka < 16; ++ka) {
-            const float2 w = tw[((t * ka) & 255) * N2];
-            const cf r = cmul(v[ka], cf{w.x, -w.y});
+            const float2 w = tw256[e256];
+            e256 = (e256 + t) & 255;
+            const cf r = cmulc(v[ka], cf{w.x, w.y});       // * W_256^{t ka}
             xbuf[ka * kRowPad + t * kPairs + c] = make_float2(r.x, r.y);
         }
         __syncthreads();
@@ -150,39 +180,35 @@ spu_fft256(const T* __restrict__ x, int N, int D, int64_t row_stride, int sigma,
         fft16<false>(v);                         // over the residue -> kb ; v[kb] = Y[t + 16 kb]
 #pragma unroll
         for (int kb = 0; kb < 16; ++kb) {
-            if (inband & (1u << kb)) {
-                const float2 w = tw[ph[kb]];
-                const cf r = cmul(v[kb], cf{w.x, -w.y});
-                F[kb] = F[kb] + r;
-            }
-            ph[kb] += kpos[kb];
-            if (ph[kb] >= N) ph[kb] -= N;
+            const float2 w = tw[ph[kb]];
+            F[kb] = F[kb] + cmulc(v[kb], cf{w.x, w.y});    // * W_N^{k n2}
+            advance(kb);
         }
     }
     // ------------------------------------------------------------------ mask (Eq. 5-6) with the 1/N of Eq. 7
 #pragma unroll
     for (int kb = 0; kb < 16; ++kb) {
         const int k1 = t + 16 * kb;
-        const int f = k1 <= sigma ? k1 : 256 - k1;
-        const float g = (inband & (1u << kb)) ? gm[f] : 0.f;
+        const bool lo = k1 <= sigma, hi = k1 >= 256 - sigma;
+        const float g = (lo || hi) ? gm[lo ? k1 : 256 - k1] : 0.f;
         F[kb] = {F[kb].x * g, F[kb].y * g};
         ph[kb] = 0;
     }
     // ------------------------------------------------------------------ inverse (Eq. 7) and energy (Eq. 8)
-    float* pout = partial + ((int64_t)b * n_tiles + tile) * N;
     for (int n2 = 0; n2 < N2; ++n2) {
         cf v[16];
 #pragma unroll
         for (int kb = 0; kb < 16; ++kb) {
             const float2 w = tw[ph[kb]];
             v[kb] = cmul(F[kb], cf{w.x, w.y});   // F[k] W_N^{-k n2}
-            ph[kb] += kpos[kb];
-            if (ph[kb] >= N) ph[kb] -= N;
+            advance(kb);
         }
         fft16<true>(v);                          // over kb -> residue s
+        int e256 = 0;
 #pragma unroll
         for (int s = 0; s < 16; ++s) {
-            const float2 w = tw[((t * s) & 255) * N2];
+            const float2 w = tw256[e256];
+            e256 = (e256 + t) & 255;
             const cf r = cmul(v[s], cf{w.x, w.y});
             xbuf[s * kRowPad + t * kPairs + c] = make_float2(r.x, r.y);
         }
@@ -193,23 +219,23 @@ spu_fft256(const T* __restrict__ x, int N, int D, int64_t row_stride, int sigma,
         fft16<true>(v);                          // over ka -> j ; v[j] = z'[N2 (16 j + t) + n2]
         float e[16];
 #pragma unroll
-        for (int j = 0; j < 16; ++j) e[j] = fmaf(v[j].x, v[j].x, v[j].y * v[j].y);
-        // sum over the 16 pairs (lanes c) while transposing: afterwards lane c holds the total of j = c
+        for (int j = 0; j < 16; ++j) e[j] = row16_sum(fmaf(v[j].x, v[j].x, v[j].y * v[j].y));   // over the 16 pairs
+        if (c == 0) {
+            float4* dst = reinterpret_cast<float4*>(eperm + (n2 * 16 + t) * 16);
 #pragma unroll
-        for (int h = 8; h >= 1; h >>= 1) {
-            const bool up = (c & h) != 0;
-#pragma unroll
-            for (int i = 0; i < h; ++i) {
-                const float send = up ? e[i] : e[i + h];
-                const float keep = up ? e[i + h] : e[i];
-                e[i] = keep + __shfl_xor(send, h, kWave);
-            }
+            for (int q = 0; q < 4; ++q) dst[q] = make_float4(e[4 * q], e[4 * q + 1], e[4 * q + 2], e[4 * q + 3]);
         }
-        pout[N2 * (16 * c + t) + n2] = e[0];
+    }
+    __syncthreads();
+    float* pout = partial + ((int64_t)b * n_tiles + tile) * N;
+    for (int n = tid; n < N; n += 256) {         // n = N2 (16 j + t') + n2
+        const int n2 = POW2 ? (n & (N2 - 1)) : n % N2;
+        const int q = (n - n2) / N2;
+        pout[n] = eperm[(n2 * 16 + (q & 15)) * 16 + (q >> 4)];
     }
 }
 
-static size_t fft_lds_bytes(int N) { return sizeof(float2) * (size_t)(16 * kRowPad + N); }
+static size_t fft_lds_bytes(int N) { return sizeof(float2) * (size_t)(16 * kRowPad + N + 256) + sizeof(float) * (size_t)N; }
 
 bool spu_fft_supported(int N, int sigma)
 {
@@ -221,13 +247,16 @@ luvc_status spu_score_fft(const void* x, int B, int N, int D, int64_t row_stride
 {
     const dim3 grid((unsigned)n_tiles, (unsigned)B);
     const size_t lds = fft_lds_bytes(N);
-    if (dt == LUVC_F32) {
-        const int aligned = (row_stride % 2 == 0) && ((uintptr_t)x % 8 == 0) && (D % 2 == 0);
-        hipLaunchKernelGGL((spu_fft256<float>), grid, dim3(256), lds, st, (const float*)x, N, D, row_stride, sigma, aligned, tw, gm, partial);
-    } else {
-        const int aligned = (row_stride % 2 == 0) && ((uintptr_t)x % 4 == 0) && (D % 2 == 0);
-        hipLaunchKernelGGL((spu_fft256<bf16_t>), grid, dim3(256), lds, st, (const bf16_t*)x, N, D, row_stride, sigma, aligned, tw, gm, partial);
-    }
+    const bool pow2 = (N & (N - 1)) == 0;
+    // channel pairs are fetched with one access when every pair is naturally aligned
+    const size_t pair_bytes = dt == LUVC_F32 ? 8 : 4;
+    const bool aligned = (row_stride % 2 == 0) && ((uintptr_t)x % pair_bytes == 0) && (D % 2 == 0);
+#define LUVC_FFT(TT, P2, AL) hipLaunchKernelGGL((spu_fft256<TT, P2, AL>), grid, dim3(256), lds, st, (const TT*)x, N, D, row_stride, sigma, tw, gm, partial)
+#define LUVC_FFT_T(TT) do { if (pow2) { if (aligned) LUVC_FFT(TT, true, true); else LUVC_FFT(TT, true, false); } \
+                            else { if (aligned) LUVC_FFT(TT, false, true); else LUVC_FFT(TT, false, false); } } while (0)
+    if (dt == LUVC_F32) LUVC_FFT_T(float); else LUVC_FFT_T(bf16_t);
+#undef LUVC_FFT_T
+#undef LUVC_FFT
     return check_launch("spu score (fft)");
 }
 
