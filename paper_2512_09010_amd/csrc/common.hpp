@@ -30,23 +30,18 @@ __device__ __forceinline__ uint16_t f32_to_bf16(float f)
     return (uint16_t)(u >> 16);
 }
 
-// fp64 -> bf16 with a single rounding.  Rounding to fp32 first and then to bf16 differs from the
-// direct rounding only when the fp32 value lands exactly on a bf16 midpoint although v was not on
-// it; then the fp32 value is nudged one step back toward v before the nearest-even rounding.
-// Branch-free.
+// fp64 -> bf16 with a single nearest-even rounding, branch-free.  Adding and subtracting
+// C = sign(v) * 2^(e + 45), e = exponent of v clamped at the smallest normal bf16 exponent, makes the
+// fp64 adder round v to a multiple of 2^(e - 7): 8 significant bits for normal results, the fixed
+// quantum 2^-133 for subnormal ones.  The rounded value is exact in fp32; its upper half is the bf16.
 __device__ __forceinline__ uint16_t f64_to_bf16(double v)
 {
-    const float f = (float)v;                             // nearest-even
-    uint32_t u = __float_as_uint(f);
-    const double back = (double)f;
-    const bool mid = (u & 0xffffu) == 0x8000u;
-    const bool finite = (u & 0x7f800000u) != 0x7f800000u;
-    // |f| > |v|: f was rounded away from zero, step the magnitude down; |f| < |v|: step it up
-    const int adj = (fabs(back) > fabs(v)) ? -1 : ((fabs(back) < fabs(v)) ? 1 : 0);
-    u += (mid && finite) ? (uint32_t)adj : 0u;
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);   // NaN stays NaN
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
+    const uint32_t hi = (uint32_t)__double2hiint(v);
+    uint32_t ef = hi & 0x7ff00000u;
+    ef = ef < (897u << 20) ? (897u << 20) : ef;
+    const double C = __hiloint2double((int)((hi & 0x80000000u) | (ef + (45u << 20))), 0);
+    const double r = (v + C) - C;
+    return (uint16_t)(__float_as_uint((float)r) >> 16);
 }
 
 template <typename T> struct io_traits;

@@ -19,7 +19,7 @@ namespace luvc {
 
 namespace {
 
-struct Scal { double na, nb, dab, dbc; };     // |a|^2, |b|^2, a.b, b.c of one slot
+struct Scal { double na, nb, dab, dbc; };     // |a|^2, |b|^2, a.b, b.c of one slot (na, nb become 1/|a|, 1/|b| before the exchange)
 
 template <typename T, int NCH>
 struct Tok {
@@ -97,21 +97,22 @@ __device__ __forceinline__ void forget(Tok<T, NCH>& t)
     }
 }
 
-__device__ __forceinline__ double clamp_norm(double n2)
+// 1 / max(|x|, 1e-12) from the squared norm
+__device__ __forceinline__ double inv_norm(double n2)
 {
     const double n = sqrt(n2);
-    return n < 1e-12 ? 1e-12 : n;
+    return 1.0 / (n < 1e-12 ? 1e-12 : n);
 }
 
-// Does the source (squared norm ns) go to its LEFT destination?  tie -> left (lower position)
-__device__ __forceinline__ bool source_goes_left(bool has_left, bool has_right, double ns,
-                                                 double dot_l, double nl, double dot_r, double nr)
+// Does a source go to its LEFT destination?  Cosines are formed as (dot * 1/|src|) * 1/|dst| - the
+// same expression, on the same bits, in both wavefronts that look at a source; tie -> left.
+__device__ __forceinline__ bool source_goes_left(bool has_left, bool has_right, double inv_src,
+                                                 double dot_l, double inv_l, double dot_r, double inv_r)
 {
     if (!has_left) return false;
     if (!has_right) return true;
-    const double n = clamp_norm(ns);
-    const double sl = dot_l / (n * clamp_norm(nl));
-    const double sr = dot_r / (n * clamp_norm(nr));
+    const double sl = (dot_l * inv_src) * inv_l;
+    const double sr = (dot_r * inv_src) * inv_r;
     return !(sr > sl);
 }
 
@@ -127,7 +128,7 @@ oim_halve(const T* __restrict__ x, const int32_t* __restrict__ sizes_in, int H, 
     using tr = io_traits<T>;
     constexpr int V = tr::kVec;
     __shared__ Scal sc[8];
-    __shared__ double halo[5];                    // left: |l|^2, l.a0 ; right: |c|^2, |r|^2, c.r
+    __shared__ double halo[5];                    // left: 1/|l|, l.a0 ; right: 1/|c|, 1/|r|, c.r
 
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -177,15 +178,15 @@ oim_halve(const T* __restrict__ x, const int32_t* __restrict__ sizes_in, int H, 
             double u0 = 0.0, u1 = 0.0, u2 = 0.0;
             sweep<T, NCH, false, false>(A, Bt, C, Hx, me, u0, u1, u2);
         }
-        me.na = wave_sum(me.na); me.nb = wave_sum(me.nb); me.dab = wave_sum(me.dab);
+        me.na = inv_norm(wave_sum(me.na)); me.nb = inv_norm(wave_sum(me.nb)); me.dab = wave_sum(me.dab);
         if (has_c) me.dbc = wave_sum(me.dbc);
         if (need_l) {
-            nl = wave_sum(nl); dl = wave_sum(dl);
+            nl = inv_norm(wave_sum(nl)); dl = wave_sum(dl);
             if (lane == 0) { halo[0] = nl; halo[1] = dl; }
         }
         if (need_r) {
-            nc = wave_sum(nc);
-            if (has_r) { nr = wave_sum(nr); dcr = wave_sum(dcr); }
+            nc = inv_norm(wave_sum(nc));
+            if (has_r) { nr = inv_norm(wave_sum(nr)); dcr = wave_sum(dcr); }
             if (lane == 0) { halo[2] = nc; halo[3] = nr; halo[4] = dcr; }
         }
         if (lane == 0) sc[w] = me;
@@ -197,7 +198,7 @@ oim_halve(const T* __restrict__ x, const int32_t* __restrict__ sizes_in, int H, 
     forget<T, NCH>(C);
 
     // ---- source a = 2j: right (into b) unless its left destination 2j-1 is at least as similar
-    double l_nb = 0.0, l_dbc = 0.0;               // |2j-1|^2 and <2j-1, 2j>
+    double l_nb = 0.0, l_dbc = 0.0;               // 1/|2j-1| and <2j-1, 2j>
     if (pa >= 1) {
         if (w > 0) { l_nb = sc[w - 1].nb; l_dbc = sc[w - 1].dbc; }
         else { l_nb = halo[0]; l_dbc = halo[1]; }
