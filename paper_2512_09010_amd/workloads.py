@@ -18,7 +18,6 @@ from dataclasses import dataclass, field
 from typing import List, Tuple
 
 import numpy as np
-from scipy.ndimage import gaussian_filter1d
 
 AXIS_H, AXIS_W = 0, 1
 BASE_SEED = 20251209
@@ -56,22 +55,29 @@ def widen(a: np.ndarray, dtype: str) -> np.ndarray:
 # ----------------------------------------------------------------------------- random fields
 
 def _blur_wrap(a: np.ndarray, ell: float, axis: int) -> np.ndarray:
-    """Gaussian blur exp(-t^2 / 2 ell^2), truncated at +-4 ell, periodic, rescaled to keep unit variance."""
+    """Periodic blur with exp(-t^2 / 2 ell^2) truncated at +-4 ell, rescaled to keep unit variance.
+
+    The truncated kernel is wrapped onto the axis and applied as a circular convolution (through a
+    real FFT along the axis, chunked to bound memory), which is exact for any kernel length.
+    """
     if ell <= 0:
         return a
-    out = gaussian_filter1d(a, sigma=ell, axis=axis, mode="wrap", truncate=4.0)
+    n = a.shape[axis]
     r = int(4.0 * ell + 0.5)
     t = np.arange(-r, r + 1, dtype=np.float64)
     k = np.exp(-0.5 * (t / ell) ** 2)
     k /= k.sum()
-    n = a.shape[axis]
-    if 2 * r + 1 > n:                       # the kernel wraps onto itself on a short axis
-        kk = np.zeros(n)
-        for i, v in zip(np.arange(-r, r + 1) % n, k):
-            kk[i] += v
-        k = kk
-    out /= np.float32(np.sqrt((k ** 2).sum()))
-    return out
+    kk = np.zeros(n)
+    np.add.at(kk, np.arange(-r, r + 1) % n, k)                  # the kernel may wrap onto itself on a short axis
+    kk /= np.sqrt((kk ** 2).sum())                              # i.i.d. N(0,1) in -> unit variance out
+    Kf = np.fft.rfft(kk)
+    a = np.ascontiguousarray(np.moveaxis(a, axis, -1))
+    out = np.empty(a.shape, a.dtype)
+    flat_in, flat_out = a.reshape(-1, n), out.reshape(-1, n)
+    step = max(1, (1 << 22) // n)
+    for i in range(0, flat_in.shape[0], step):
+        flat_out[i:i + step] = np.fft.irfft(np.fft.rfft(flat_in[i:i + step], axis=-1) * Kf, n=n, axis=-1)
+    return np.ascontiguousarray(np.moveaxis(out, -1, axis))
 
 
 def grf(rng: np.random.Generator, shape: Tuple[int, ...], ell: float, axes=(-3, -2)) -> np.ndarray:

@@ -7,7 +7,7 @@ from paper_2512_09010_amd import workloads as wl
 # Tolerances of the parity bar: relative, per element, on values stored in the I/O dtype.
 RTOL = {"f32": 1e-5, "bf16": 2e-2}
 OIM_MARGIN = 1e-10      # fp64-accumulated cosines: below this gap a decision may legitimately differ
-SPU_MARGIN = 1e-5       # relative gap of fp32 scores at the keep boundary
+SPU_MARGIN = 2e-6       # relative gap of fp32 scores at the keep boundary (measured score error <= 1.3e-7, bound ~1e-6)
 
 
 def to_dev(a: np.ndarray, dtype: str) -> torch.Tensor:

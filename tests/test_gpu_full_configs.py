@@ -1,0 +1,85 @@
+"""GPU parity at the FULL sizes of the five benchmark configurations, element by element against
+the CPU oracle, in the launch configuration bench.py times (preallocated outputs, one workspace,
+same calls).  Inputs are the seeded synthetic fields of paper_2512_09010_amd.workloads; if a seed
+happens to produce a decision whose gap is below the arithmetic error (see gpu_util), the seed is
+advanced by 1000, as the design notes describe, and the seed used is printed."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2512_09010_amd import binding as lv
+from paper_2512_09010_amd import workloads as wl
+from gpu_util import OIM_MARGIN, SPU_MARGIN, round_mode, to_dev, to_host_f64
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("i", [0, 1, 2, 3, 4])
+def test_oim_full(oracle, i):
+    w = wl.workload(i)
+    for reseed in range(4):
+        x = wl.oim_input(w, reseed)
+        print(f"[full oim] {w.name} reseed={reseed} shape={x.shape}", flush=True)
+        cur_ref, sizes_ref = wl.widen(x, w.dtype), None
+        cur_dev, sizes_dev = to_dev(x, w.dtype), None
+        margin = np.inf
+        refs, outs = [], []
+        for passes in w.oim_calls:
+            ref = oracle.oim_merge(cur_ref, passes, sizes=sizes_ref, round_mode=round_mode(oracle, w.dtype))
+            out = lv.luvc_oim_merge(cur_dev, passes, sizes=sizes_dev)
+            torch.cuda.synchronize()
+            margin = min(margin, ref["margin"])
+            refs.append(ref)
+            outs.append(out)
+            cur_ref, sizes_ref = ref["x"], ref["sizes"]
+            # the next call reads the oracle's bits on both sides, so a call is judged on identical inputs
+            cur_dev = to_dev(wl.cast_io(ref["x"].astype(np.float32), w.dtype), w.dtype)
+            sizes_dev = torch.from_numpy(ref["sizes"].astype(np.int32)).cuda()
+        if margin > OIM_MARGIN:
+            break
+        print(f"  smallest decision gap {margin:.3e} <= {OIM_MARGIN}: reseeding", flush=True)
+    else:
+        pytest.fail("no seed with unique decisions found")
+    print(f"  smallest decision gap {margin:.3e}", flush=True)
+    for ref, out in zip(refs, outs):
+        np.testing.assert_array_equal(out["merged_map"].cpu().numpy(), ref["merged_map"])
+        np.testing.assert_array_equal(out["kept_map"].cpu().numpy(), ref["kept_map"])
+        np.testing.assert_array_equal(out["sizes"].cpu().numpy().astype(np.int64), ref["sizes"])
+        got = to_host_f64(out["x"])
+        if w.dtype == "bf16":
+            np.testing.assert_array_equal(got, ref["x"])                       # fp64 merge, one rounding: same bits
+        else:
+            np.testing.assert_allclose(got, ref["x"], rtol=1e-5, atol=0)
+    Ho, Wo = w.out_grid()
+    assert tuple(outs[-1]["x"].shape) == (w.grids, Ho, Wo, w.D)
+
+
+@pytest.mark.parametrize("i", [0, 1, 2, 3, 4])
+def test_spu_full(oracle, i):
+    w = wl.workload(i)
+    for reseed in range(4):
+        x = wl.spu_input(w, reseed)
+        print(f"[full spu] {w.name} reseed={reseed} shape={x.shape} sigma={w.sigma} n_keep={w.n_keep}", flush=True)
+        xw = wl.widen(x, w.dtype)
+        ref = oracle.spu_score(xw, w.sigma, True)
+        full = oracle.spu_prune(ref, w.n_keep, xw)
+        if full["margin"] > SPU_MARGIN:
+            break
+        print(f"  keep-boundary gap {full['margin']:.3e} <= {SPU_MARGIN}: reseeding", flush=True)
+    else:
+        pytest.fail("no seed with a unique keep set found")
+    xd = to_dev(x, w.dtype)
+    code = lv.LUVC_BF16 if w.dtype == "bf16" else lv.LUVC_F32
+    ws = torch.empty(lv.luvc_spu_workspace_bytes(w.spu_B, w.spu_N, w.spu_D, code, w.sigma), dtype=torch.uint8, device="cuda")
+    scores = torch.empty((w.spu_B, w.spu_N), dtype=torch.float32, device="cuda")
+    lv.luvc_spu_score(xd, w.sigma, True, workspace=ws, out=scores)
+    pr = lv.luvc_spu_prune(xd, scores, w.n_keep)
+    torch.cuda.synchronize()
+    got = scores.cpu().numpy().astype(np.float64)
+    rel = np.abs(got - ref) / np.abs(ref)
+    print(f"  keep-boundary gap {full['margin']:.3e}; worst relative score error {rel.max():.3e}", flush=True)
+    assert rel.max() <= 1e-5                                                    # fp32 bar, met by bf16 inputs as well
+    kept = pr["kept_idx"].cpu().numpy()
+    np.testing.assert_array_equal(kept, oracle.spu_prune(got, w.n_keep)["kept_idx"])   # selection exact on own scores
+    np.testing.assert_array_equal(kept, full["kept_idx"])                               # and equal to the oracle's keep set
+    np.testing.assert_array_equal(to_host_f64(pr["x"]), full["x"])                      # original tokens, bit copies
