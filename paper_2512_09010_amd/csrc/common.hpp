@@ -66,6 +66,18 @@ template <> struct io_traits<bf16_t> {
     }
 };
 
+// ------------------------------------------------------------------ XCD-aware workgroup order
+// Workgroups are dealt to the 8 XCDs round-robin by linear id, and each XCD has its own L2.  This
+// maps linear id g of G workgroups to a work item such that every XCD walks one contiguous range
+// of work items in order: neighbouring items (which share halo tokens or cache lines) then meet in
+// the same L2 at about the same time.
+__device__ __forceinline__ unsigned xcd_contiguous(unsigned g, unsigned G)
+{
+    constexpr unsigned kXcd = 8;
+    const unsigned k = g % kXcd, i = g / kXcd, q = G / kXcd, r = G % kXcd;
+    return k * q + (k < r ? k : r) + i;
+}
+
 // ------------------------------------------------------------------ wave64 reductions (all lanes get the result)
 __device__ __forceinline__ double wave_sum(double v)
 {

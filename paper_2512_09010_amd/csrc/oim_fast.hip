@@ -135,9 +135,10 @@ oim_halve(const T* __restrict__ x, const int32_t* __restrict__ sizes_in, int H, 
     const int len = axis ? W : H, nlines = axis ? H : W;
     const int nd = len >> 1;                      // destinations = output slots per line
     const int Wo = axis ? nd : W;
-    const int tile = blockIdx.x % tiles_per_line;
-    const int line = (blockIdx.x / tiles_per_line) % nlines;
-    const int b = blockIdx.x / (tiles_per_line * nlines);
+    const unsigned item = xcd_contiguous(blockIdx.x, gridDim.x);   // tiles of a line stay on one XCD
+    const int tile = item % tiles_per_line;
+    const int line = (item / tiles_per_line) % nlines;
+    const int b = item / (tiles_per_line * nlines);
     const int j0 = tile * slots_per_tile;
     const int nslot = min(slots_per_tile, nd - j0);        // live waves of this workgroup
     const int j = j0 + w;

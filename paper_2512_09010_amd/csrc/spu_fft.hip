@@ -118,7 +118,10 @@ spu_fft256(const T* __restrict__ x, int N, int D, int64_t row_stride, int sigma,
     float2* tw256 = tw + N;                      // [256]  (cos, sin)(2 pi i / 256)
     float* eperm = reinterpret_cast<float*>(tw256 + 256);   // [N2][16 t][16 j] energies of this tile
     const int tid = threadIdx.x, c = tid & 15, t = tid >> 4;
-    const int tile = blockIdx.x, n_tiles = gridDim.x, b = blockIdx.y;
+    // neighbouring channel tiles share 128-byte lines of every token row: keep them on one XCD
+    const int n_tiles = gridDim.x;
+    const unsigned item = xcd_contiguous(blockIdx.x + gridDim.x * blockIdx.y, gridDim.x * gridDim.y);
+    const int tile = item % n_tiles, b = item / n_tiles;
     const int N2 = N >> 8;
     for (int i = tid; i < N; i += 256) tw[i] = tw_g[i];
     tw256[tid] = tw_g[tid * N2];
