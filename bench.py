@@ -128,10 +128,21 @@ def main():
     prune_bytes = 2 * w.spu_B * w.n_keep * w.spu_D * es
     alg = dict(oim=oim_bytes, spu_score=score_bytes, spu_prune=prune_bytes)
     names = ["oim", "spu_score", "spu_prune"]
+    kernels = {"oim": "oim_halve x2 per OIM call (W pass, H pass) + map composition", "spu_score": "spu_fft256 (+ tables, finish)",
+               "spu_prune": "spu_select + spu_gather"}
     dom = int(np.argmax(seg_mean))
     achieved = alg[names[dom]] / (seg_mean[dom] * 1e-3) / 1e9
-    roofline = {"bound": "hbm", "kernel": names[dom], "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+    # HBM bytes per step of the dominant call from the committed rocprofv3 --pmc summary (FETCH_SIZE / WRITE_SIZE,
+    # scaled by the copy-kernel calibration stated there); null when no summary covers this workload
+    traffic = None
+    try:
+        with open(os.path.join(ROOT, "profiles", "hbm_traffic.json")) as f:
+            t = json.load(f)[w.name][names[dom]]
+        traffic = {"read_bytes": t["read_bytes"], "write_bytes": t["write_bytes"], "total_bytes": t["read_bytes"] + t["write_bytes"]}
+    except (OSError, KeyError, ValueError):
+        pass
+    roofline = {"bound": "hbm", "kernel": kernels[names[dom]], "call": names[dom], "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                 "algorithmic_bytes": alg[names[dom]], "avg_ms": round(float(seg_mean[dom]), 5),
                 "whole_step": {"algorithmic_bytes": sum(alg.values()),
                                "achieved": round(sum(alg.values()) / (ms_per_step * 1e-3) / 1e9, 1),
@@ -159,7 +170,7 @@ def cpu_baseline(w, x_oim_host, x_spu_host):
     import oracle
     from paper_2512_09010_amd import workloads as wl
 
-    n_s = min(w.spu_B, 4)                                   # SPU samples (each an independent OpenMP job)
+    n_s = min(w.spu_B, 8)                                   # SPU samples (each an independent OpenMP job)
     frac = n_s / w.spu_B
     n_g = max(1, int(round(w.grids * frac)))
     rm = oracle.ROUND_BF16 if w.dtype == "bf16" else oracle.ROUND_F32
