@@ -5,11 +5,19 @@
 // slot j of a line is destination 2j+1 and no per-line ranking is needed.  One wavefront produces
 // one output token: it keeps source a = 2j, destination b = 2j+1 and the next source c = 2j+2 in
 // registers (each token is read once per use, 16 bytes per lane per access), accumulates the
-// squared norms and the two neighbour dot products in fp64, trades those four scalars with the
+// squared norms and the two neighbour dot products, trades those four scalars with the
 // neighbouring wavefronts of its workgroup through LDS, decides where a and c go, and writes the
 // size-weighted mean.  The waves at the two ends of a workgroup's run of slots evaluate the one
 // or two halo tokens they need themselves, with the same routine, so the decision about a source
 // is bit-identical in both wavefronts that look at it.
+//
+// Decisions are fp64 decisions, reached in two steps.  A screening sweep forms the cosines in fp32
+// (packed bf16 dot instructions) with a rigorous error bound tau; a source whose two cosines differ
+// by more than tau goes where the fp32 values say - the fp64 values cannot say otherwise.  If any
+// decision of the workgroup is closer than tau (or an exact tie), every wavefront of the workgroup
+// repeats the sweep in fp64 and the fp64 cosines decide.  The verdict "closer than tau" is a
+// function of the screening values of that source alone, which are the same bits in every
+// wavefront and workgroup that looks at it, so neighbours always agree on a shared source.
 #include <cstdlib>
 
 #include "common.hpp"
@@ -85,6 +93,81 @@ __device__ __forceinline__ void sweep(const Tok<T, NCH>& A, const Tok<T, NCH>& B
     }
 }
 
+// ---- fp32 screening
+struct ScalF { float ia, ib, dab, dbc; };      // 1/|a|, 1/|b|, a.b, b.c of one slot
+
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+
+// acc += <x, y> over one 16-byte chunk in fp32
+template <typename T> __device__ __forceinline__ float dot_chunk32(float acc, const typename io_traits<T>::vec_t& x, const typename io_traits<T>::vec_t& y);
+template <> __device__ __forceinline__ float dot_chunk32<bf16_t>(float acc, const uint4& x, const uint4& y)
+{
+    const uint32_t xs[4] = {x.x, x.y, x.z, x.w}, ys[4] = {y.x, y.y, y.z, y.w};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        bf16x2_t a, b;
+        __builtin_memcpy(&a, &xs[k], 4);
+        __builtin_memcpy(&b, &ys[k], 4);
+        acc = __builtin_amdgcn_fdot2_f32_bf16(a, b, acc, false);
+    }
+    return acc;
+}
+template <> __device__ __forceinline__ float dot_chunk32<float>(float acc, const float4& x, const float4& y)
+{
+    acc = fmaf(x.x, y.x, acc); acc = fmaf(x.y, y.y, acc); acc = fmaf(x.z, y.z, acc); acc = fmaf(x.w, y.w, acc);
+    return acc;
+}
+
+template <typename T, int NCH, bool HALO, bool LEFT>
+__device__ __forceinline__ void sweep32(const Tok<T, NCH>& A, const Tok<T, NCH>& B, const Tok<T, NCH>& C, const Tok<T, NCH>& Hx,
+                                        float& na, float& nb, float& dab, float& dbc, float& ncc, float& nhh, float& dh)
+{
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+        na = dot_chunk32<T>(na, A.v[i], A.v[i]);
+        nb = dot_chunk32<T>(nb, B.v[i], B.v[i]);
+        dab = dot_chunk32<T>(dab, A.v[i], B.v[i]);
+        dbc = dot_chunk32<T>(dbc, B.v[i], C.v[i]);
+        if (HALO) {
+            ncc = dot_chunk32<T>(ncc, C.v[i], C.v[i]);
+            nhh = dot_chunk32<T>(nhh, Hx.v[i], Hx.v[i]);
+            dh = LEFT ? dot_chunk32<T>(dh, Hx.v[i], A.v[i]) : dot_chunk32<T>(dh, C.v[i], Hx.v[i]);
+        }
+    }
+}
+
+// wave64 sum in a fixed order: DPP adds inside each row of 16 lanes, then the four rows
+__device__ __forceinline__ float wave_sum32(float v)
+{
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xf, 0xf, false));    // quad_perm [1,0,3,2]
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x4E, 0xf, 0xf, false));    // quad_perm [2,3,0,1]
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x141, 0xf, 0xf, false));   // row_half_mirror
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x140, 0xf, 0xf, false));   // row_mirror
+    v += __shfl_xor(v, 16, kWave);
+    v += __shfl_xor(v, 32, kWave);
+    return v;
+}
+
+__device__ __forceinline__ float inv_norm32(float n2)
+{
+    const float n = sqrtf(n2);
+    return 1.0f / (n < 1e-12f ? 1e-12f : n);
+}
+
+// Screening verdict for one source: +1 = left for certain, -1 = right for certain, 0 = too close to call
+__device__ __forceinline__ int screen_source(bool has_left, bool has_right, float inv_src,
+                                             float dot_l, float inv_l, float dot_r, float inv_r, float tau)
+{
+    if (!has_left) return -1;
+    if (!has_right) return 1;
+    const float sl = (dot_l * inv_src) * inv_l;
+    const float sr = (dot_r * inv_src) * inv_r;
+    const float d = sl - sr;
+    if (d > tau) return 1;
+    if (d < -tau) return -1;
+    return 0;                                   // includes NaN
+}
+
 // Hides a token's registers from value numbering: the merge phase re-widens the packed data instead
 // of keeping the fp64 copies of the similarity phase alive across the barrier (which spills).
 template <typename T, int NCH>
@@ -129,6 +212,9 @@ oim_halve(const T* __restrict__ x, const int32_t* __restrict__ sizes_in, int H, 
     constexpr int V = tr::kVec;
     __shared__ Scal sc[8];
     __shared__ double halo[5];                    // left: 1/|l|, l.a0 ; right: 1/|c|, 1/|r|, c.r
+    __shared__ ScalF scf[8];                      // the same exchange for the fp32 screening sweep
+    __shared__ float halof[6];                    // ... plus [5]: right-hand source could not be screened
+    __shared__ int redo;                          // some decision of this workgroup is too close for fp32
 
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -148,71 +234,119 @@ oim_halve(const T* __restrict__ x, const int32_t* __restrict__ sizes_in, int H, 
     const int64_t line0 = img + (axis ? (int64_t)line * W : line);    // token index of position 0
     auto tok_ptr = [&](int pos) { return x + (line0 + pos * step) * D; };
 
-    Tok<T, NCH> A, Bt, C;
+    Tok<T, NCH> A, Bt, C, Hx;
     const int pa = 2 * j, pb = 2 * j + 1, pc = 2 * j + 2;
     const bool has_c = live && pc < len;
-    Scal me{0, 0, 0, 0};
+    // the end waves of the workgroup also need one token beyond its run of slots
+    const bool need_l = live && (w == 0) && pa >= 1;
+    const bool need_r = live && (w == nslot - 1) && has_c;  // c's own right neighbour, if any, decides with us
+    const bool has_r = need_r && pc + 1 < len;
+    // error bound of a screening cosine: (NCH*V + 8) roundings of at most 2^-23 each on the dot product,
+    // the same on each norm, doubled for safety; two cosines are compared
+    const float tau = 16.0f * (float)(NCH * V + 8) * 5.9604645e-8f;
+    if (threadIdx.x == 0) redo = 0;
     if (live) {
-        // the end waves of the workgroup also need one token beyond its run of slots
-        const bool need_l = (w == 0) && pa >= 1;
-        const bool need_r = (w == nslot - 1) && has_c;     // c's own right neighbour, if any, decides with us
-        const bool has_r = need_r && pc + 1 < len;
-        Tok<T, NCH> Hx;
         load_tok<T, NCH>(A, tok_ptr(pa), D, lane);
         load_tok<T, NCH>(Bt, tok_ptr(pb), D, lane);
         load_tok<T, NCH>(C, tok_ptr(has_c ? pc : pb), D, lane, has_c);
         load_tok<T, NCH>(Hx, tok_ptr(need_l ? pa - 1 : (has_r ? pc + 1 : pb)), D, lane, need_l || has_r);
-        double nl = 0.0, dl = 0.0, nc = 0.0, nr = 0.0, dcr = 0.0;
-        // every accumulator sees its terms in the same (chunk, element) order in whichever wavefront
-        // evaluates it, so a dot product shared by two wavefronts has the same bits in both
+        float na = 0.f, nb = 0.f, dab = 0.f, dbc = 0.f, ncc = 0.f, nhh = 0.f, dh = 0.f;
+        if (need_l) sweep32<T, NCH, true, true>(A, Bt, C, Hx, na, nb, dab, dbc, ncc, nhh, dh);
+        else if (need_r) sweep32<T, NCH, true, false>(A, Bt, C, Hx, na, nb, dab, dbc, ncc, nhh, dh);
+        else sweep32<T, NCH, false, false>(A, Bt, C, Hx, na, nb, dab, dbc, ncc, nhh, dh);
+        ScalF f;
+        f.ia = inv_norm32(wave_sum32(na)); f.ib = inv_norm32(wave_sum32(nb));
+        f.dab = wave_sum32(dab); f.dbc = wave_sum32(dbc);
+        if (lane == 0) scf[w] = f;
         if (need_l) {
-            sweep<T, NCH, true, true>(A, Bt, C, Hx, me, nc, nl, dl);
-            if (has_r) {                                    // single-wave workgroup: the other end as well
-                load_tok<T, NCH>(Hx, tok_ptr(pc + 1), D, lane);
-                double unused = 0.0;
-                Scal tmp{0, 0, 0, 0};
-                sweep<T, NCH, true, false>(A, Bt, C, Hx, tmp, unused, nr, dcr);
-            }
-        } else if (need_r) {
-            sweep<T, NCH, true, false>(A, Bt, C, Hx, me, nc, nr, dcr);
-        } else {
-            double u0 = 0.0, u1 = 0.0, u2 = 0.0;
-            sweep<T, NCH, false, false>(A, Bt, C, Hx, me, u0, u1, u2);
-        }
-        me.na = inv_norm(wave_sum(me.na)); me.nb = inv_norm(wave_sum(me.nb)); me.dab = wave_sum(me.dab);
-        if (has_c) me.dbc = wave_sum(me.dbc);
-        if (need_l) {
-            nl = inv_norm(wave_sum(nl)); dl = wave_sum(dl);
-            if (lane == 0) { halo[0] = nl; halo[1] = dl; }
+            const float il = inv_norm32(wave_sum32(nhh)), dl = wave_sum32(dh);
+            if (lane == 0) { halof[0] = il; halof[1] = dl; }
         }
         if (need_r) {
-            nc = inv_norm(wave_sum(nc));
-            if (has_r) { nr = inv_norm(wave_sum(nr)); dcr = wave_sum(dcr); }
-            if (lane == 0) { halo[2] = nc; halo[3] = nr; halo[4] = dcr; }
+            const float ic = inv_norm32(wave_sum32(ncc));
+            // a one-wave workgroup holds its left halo in Hx: its right-hand source is then sent to the fp64 sweep
+            const bool unknown = need_l && has_r;
+            const float ir = (has_r && !unknown) ? inv_norm32(wave_sum32(nhh)) : 0.f;
+            const float dcr = (has_r && !unknown) ? wave_sum32(dh) : 0.f;
+            if (lane == 0) { halof[2] = ic; halof[3] = ir; halof[4] = dcr; halof[5] = unknown ? 1.f : 0.f; }
         }
-        if (lane == 0) sc[w] = me;
     }
     __syncthreads();
+    int va = -1, vc = 0;                          // screening verdicts for a and c (see screen_source)
+    if (live) {
+        const ScalF me = scf[w];
+        float l_ib = 0.f, l_dbc = 0.f;
+        if (pa >= 1) {
+            if (w > 0) { l_ib = scf[w - 1].ib; l_dbc = scf[w - 1].dbc; }
+            else { l_ib = halof[0]; l_dbc = halof[1]; }
+        }
+        va = screen_source(pa >= 1, true, me.ia, l_dbc, l_ib, me.dab, me.ib, tau);
+        if (has_c) {
+            if (w + 1 < nslot) vc = screen_source(true, pc + 1 < len, scf[w + 1].ia, me.dbc, me.ib, scf[w + 1].dab, scf[w + 1].ib, tau);
+            else vc = halof[5] != 0.f ? 0 : screen_source(true, pc + 1 < len, halof[2], me.dbc, me.ib, halof[4], halof[3], tau);
+        } else {
+            vc = -1;
+        }
+        if ((va == 0 || vc == 0) && lane == 0) redo = 1;
+    }
+    __syncthreads();
+    bool a_left = va > 0, c_left = vc > 0;
+    if (redo) {                                   // uniform over the workgroup: every wave repeats the sweep in fp64
+        Scal me{0, 0, 0, 0};
+        if (live) {
+            double nl = 0.0, dl = 0.0, nc = 0.0, nr = 0.0, dcr = 0.0;
+            // every accumulator sees its terms in the same (chunk, element) order in whichever wavefront
+            // evaluates it, so a dot product shared by two wavefronts has the same bits in both
+            if (need_l) {
+                sweep<T, NCH, true, true>(A, Bt, C, Hx, me, nc, nl, dl);
+                if (has_r) {                                    // single-wave workgroup: the other end as well
+                    load_tok<T, NCH>(Hx, tok_ptr(pc + 1), D, lane);
+                    double unused = 0.0;
+                    Scal tmp{0, 0, 0, 0};
+                    sweep<T, NCH, true, false>(A, Bt, C, Hx, tmp, unused, nr, dcr);
+                }
+            } else if (need_r) {
+                sweep<T, NCH, true, false>(A, Bt, C, Hx, me, nc, nr, dcr);
+            } else {
+                double u0 = 0.0, u1 = 0.0, u2 = 0.0;
+                sweep<T, NCH, false, false>(A, Bt, C, Hx, me, u0, u1, u2);
+            }
+            me.na = inv_norm(wave_sum(me.na)); me.nb = inv_norm(wave_sum(me.nb)); me.dab = wave_sum(me.dab);
+            if (has_c) me.dbc = wave_sum(me.dbc);
+            if (need_l) {
+                nl = inv_norm(wave_sum(nl)); dl = wave_sum(dl);
+                if (lane == 0) { halo[0] = nl; halo[1] = dl; }
+            }
+            if (need_r) {
+                nc = inv_norm(wave_sum(nc));
+                if (has_r) { nr = inv_norm(wave_sum(nr)); dcr = wave_sum(dcr); }
+                if (lane == 0) { halo[2] = nc; halo[3] = nr; halo[4] = dcr; }
+            }
+            if (lane == 0) sc[w] = me;
+        }
+        __syncthreads();
+        if (live) {
+            // ---- source a = 2j: right (into b) unless its left destination 2j-1 is at least as similar
+            double l_nb = 0.0, l_dbc = 0.0;               // 1/|2j-1| and <2j-1, 2j>
+            if (pa >= 1) {
+                if (w > 0) { l_nb = sc[w - 1].nb; l_dbc = sc[w - 1].dbc; }
+                else { l_nb = halo[0]; l_dbc = halo[1]; }
+            }
+            a_left = source_goes_left(pa >= 1, true, me.na, l_dbc, l_nb, me.dab, me.nb);
+            // ---- source c = 2j+2: left (into b) unless its right destination 2j+3 is strictly more similar
+            c_left = false;
+            if (has_c) {
+                double nc, nr, dcr;
+                if (w + 1 < nslot) { nc = sc[w + 1].na; nr = sc[w + 1].nb; dcr = sc[w + 1].dab; }
+                else { nc = halo[2]; nr = halo[3]; dcr = halo[4]; }
+                c_left = source_goes_left(true, pc + 1 < len, nc, me.dbc, me.nb, dcr, nr);
+            }
+        }
+    }
     if (!live) return;
     forget<T, NCH>(A);
     forget<T, NCH>(Bt);
     forget<T, NCH>(C);
-
-    // ---- source a = 2j: right (into b) unless its left destination 2j-1 is at least as similar
-    double l_nb = 0.0, l_dbc = 0.0;               // 1/|2j-1| and <2j-1, 2j>
-    if (pa >= 1) {
-        if (w > 0) { l_nb = sc[w - 1].nb; l_dbc = sc[w - 1].dbc; }
-        else { l_nb = halo[0]; l_dbc = halo[1]; }
-    }
-    const bool a_left = source_goes_left(pa >= 1, true, me.na, l_dbc, l_nb, me.dab, me.nb);
-    // ---- source c = 2j+2: left (into b) unless its right destination 2j+3 is strictly more similar
-    bool c_left = false;
-    if (has_c) {
-        double nc, nr, dcr;
-        if (w + 1 < nslot) { nc = sc[w + 1].na; nr = sc[w + 1].nb; dcr = sc[w + 1].dab; }
-        else { nc = halo[2]; nr = halo[3]; dcr = halo[4]; }
-        c_left = source_goes_left(true, pc + 1 < len, nc, me.dbc, me.nb, dcr, nr);
-    }
     const bool take_a = !a_left, take_c = c_left;
 
     const int64_t ta = line0 + pa * step, tb = line0 + pb * step, tc = line0 + pc * step;
