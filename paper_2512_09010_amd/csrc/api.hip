@@ -189,27 +189,42 @@ luvc_status luvc_oim_merge(const void* x, const int32_t* sizes_in, int B, int H,
     const void* cur_x = x;
     const int32_t* cur_s = sizes_in;
     const int32_t* cur_k = nullptr;
+    // launches of the call: a pair of halving passes on different axes runs as one launch
+    struct Step { int first, count; };
+    Step steps[kMaxPasses];
+    int n_steps = 0;
+    for (int i = 0; i < pl.n;) {
+        const bool pair = i + 1 < pl.n && oim_pair_supported(pl.h[i], pl.w[i], D, dtype, passes[i].axis, passes[i].m,
+                                                             passes[i + 1].axis, passes[i + 1].m, vec);
+        steps[n_steps++] = Step{i, pair ? 2 : 1};
+        i += pair ? 2 : 1;
+    }
     const int32_t* maps[kMaxPasses];
     int32_t n_in[kMaxPasses];
-    for (int i = 0; i < pl.n; ++i) {
-        const bool last = i + 1 == pl.n;
-        void* ox = last ? x_out : (void*)(ws + L.xbuf[i & 1]);
-        int32_t* os = last ? sizes_out : (int32_t*)(ws + L.sbuf[i & 1]);
-        int32_t* ok = last ? kept_map : (int32_t*)(ws + L.kbuf[i & 1]);
-        int32_t* pm = (int32_t*)(ws + L.maps[i]);
-        maps[i] = pm;
-        n_in[i] = pl.h[i] * pl.w[i];
-        const luvc_status rc =
-            oim_halve_supported(pl.h[i], pl.w[i], D, dtype, passes[i].axis, passes[i].m, vec)
-                ? oim_halve_pass(cur_x, cur_s, B, pl.h[i], pl.w[i], D, dtype, passes[i].axis, ox, os, pm, cur_k, ok, st)
-                : oim_general_pass(cur_x, cur_s, B, pl.h[i], pl.w[i], D, dtype, passes[i].axis, passes[i].m, vec,
-                                   ox, os, pm, cur_k, ok, sc, st);
+    for (int s = 0; s < n_steps; ++s) {
+        const int i = steps[s].first, e = i + steps[s].count - 1;          // passes i..e
+        const bool last = e + 1 == pl.n;
+        void* ox = last ? x_out : (void*)(ws + L.xbuf[e & 1]);
+        int32_t* os = last ? sizes_out : (int32_t*)(ws + L.sbuf[e & 1]);
+        int32_t* ok = last ? kept_map : (int32_t*)(ws + L.kbuf[e & 1]);
+        // a call that is a single launch writes its map straight to the caller
+        int32_t* pm = (n_steps == 1 && merged_map) ? merged_map : (int32_t*)(ws + L.maps[i]);
+        maps[s] = pm;
+        n_in[s] = pl.h[i] * pl.w[i];
+        luvc_status rc;
+        if (steps[s].count == 2)
+            rc = oim_pair_pass(cur_x, cur_s, B, pl.h[i], pl.w[i], D, dtype, passes[i].axis, ox, os, pm, cur_k, ok, st);
+        else if (oim_halve_supported(pl.h[i], pl.w[i], D, dtype, passes[i].axis, passes[i].m, vec))
+            rc = oim_halve_pass(cur_x, cur_s, B, pl.h[i], pl.w[i], D, dtype, passes[i].axis, ox, os, pm, cur_k, ok, st);
+        else
+            rc = oim_general_pass(cur_x, cur_s, B, pl.h[i], pl.w[i], D, dtype, passes[i].axis, passes[i].m, vec,
+                                  ox, os, pm, cur_k, ok, sc, st);
         if (rc != LUVC_OK) return rc;
         cur_x = ox;
         cur_s = os;
         cur_k = ok;
     }
-    if (merged_map) return oim_compose(maps, n_in, pl.n, B, H * W, merged_map, st);
+    if (merged_map && n_steps > 1) return oim_compose(maps, n_in, n_steps, B, H * W, merged_map, st);
     return LUVC_OK;
 }
 

@@ -26,6 +26,13 @@ luvc_status oim_halve_pass(const void* x, const int32_t* sizes_in, int B, int H,
                            void* x_out, int32_t* sizes_out, int32_t* pass_map, const int32_t* kept_prev, int32_t* kept_out,
                            hipStream_t st);
 
+// One launch for two consecutive halving passes on different axes (oim_pair.hip); pair_map sends an
+// input flat index of the first pass to an output slot of the second.
+bool oim_pair_supported(int H, int W, int D, luvc_dtype dt, int axis0, int m0, int axis1, int m1, bool vec);
+luvc_status oim_pair_pass(const void* x, const int32_t* sizes_in, int B, int H, int W, int D, luvc_dtype dt, int first_axis,
+                          void* x_out, int32_t* sizes_out, int32_t* pair_map, const int32_t* kept_prev, int32_t* kept_out,
+                          hipStream_t st);
+
 luvc_status oim_compose(const int32_t* const* maps, const int32_t* n_in, int n, int B, int n_first,
                         int32_t* merged_out, hipStream_t st);
 

@@ -57,6 +57,70 @@ def test_small_random(oracle, dtype, B, H, W, D, passes):
     run_case(oracle, x, dtype, passes, sizes=sizes, tag="random+sizes")
 
 
+def _halving(H, W, order):
+    """Schedule of halving passes: order is a string of 'W' / 'H'."""
+    passes = []
+    for ax in order:
+        if ax == "W":
+            passes.append((W_AX, (W + 1) // 2)); W -= (W + 1) // 2
+        else:
+            passes.append((H_AX, (H + 1) // 2)); H -= (H + 1) // 2
+    return passes
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("B,H,W,D,order", [
+    (2, 2, 2, 16, "WH"),          # smallest pair
+    (2, 8, 8, 64, "WH"),
+    (2, 8, 8, 64, "HW"),          # Algorithm 1 order: height first
+    (1, 9, 7, 40, "WH"),          # odd lengths on both axes: the last source of a line has one neighbour
+    (1, 7, 9, 40, "HW"),
+    (1, 3, 2, 24, "WH"),
+    (2, 12, 10, 520, "WH"),       # several 16-byte chunks per lane, ragged last chunk
+    (1, 70, 6, 48, "WH"),         # second-pass lines longer than one workgroup: runs with recomputed rows around them
+    (1, 6, 70, 48, "HW"),
+    (1, 131, 4, 32, "WH"),        # three runs, odd length
+    (1, 16, 16, 72, "WHWH"),      # two pairs in one call: maps compose
+    (1, 16, 12, 72, "HWHW"),
+    (1, 16, 16, 72, "WHW"),       # a pair followed by a single pass
+    (1, 12, 12, 1024, "WH"),      # four chunks per lane (fp32 at D=1024 is the single-image configuration)
+])
+def test_halving_pairs(oracle, dtype, B, H, W, D, order):
+    rng = np.random.default_rng(B * 1000 + H * 100 + W * 10 + D + len(order))
+    x = wl.cast_io(wl.smooth_field(rng, B, H, W, D, 2.0) + 0.1 * rng.standard_normal((B, H, W, D)).astype(np.float32), dtype)
+    passes = _halving(H, W, order)
+    run_case(oracle, x, dtype, passes, tag="pair smooth")
+    sizes = rng.integers(1, 6, (B, H, W))
+    run_case(oracle, x, dtype, passes, sizes=sizes, tag="pair smooth+sizes")
+    xr = wl.cast_io(rng.standard_normal((B, H, W, D)).astype(np.float32), dtype)
+    run_case(oracle, xr, dtype, passes, sizes=sizes, tag="pair random+sizes")
+
+
+def test_pair_without_maps(oracle):
+    # the maps are optional outputs: a call that asks for neither still produces the same tokens
+    rng = np.random.default_rng(11)
+    x = wl.cast_io(wl.smooth_field(rng, 2, 8, 8, 64, 2.0), "bf16")
+    passes = _halving(8, 8, "WH")
+    ref = oracle.oim_merge(wl.widen(x, "bf16"), passes, round_mode=round_mode(oracle, "bf16"))
+    out = lv.luvc_oim_merge(to_dev(x, "bf16"), passes, want_maps=False)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(to_host_f64(out["x"]), ref["x"])
+    np.testing.assert_array_equal(out["sizes"].cpu().numpy().astype(np.int64), ref["sizes"])
+
+
+def test_pair_close_calls(oracle):
+    # rows of near-duplicate tokens: most cosines differ by less than the fp32 screening bound, so the
+    # fp64 repeat of both passes decides; exact duplicates tie and go to the lower position
+    rng = np.random.default_rng(13)
+    base = rng.standard_normal((1, 1, 1, 256)).astype(np.float32)
+    x = base + 1e-3 * rng.standard_normal((2, 12, 12, 256)).astype(np.float32)
+    x[0, 3] = x[0, 3, 0]          # a row of identical tokens
+    x[1, :, 5] = x[1, 0, 5]       # a column of identical tokens
+    for dtype in ("bf16", "f32"):
+        for order in ("WH", "HW"):
+            run_case(oracle, wl.cast_io(x, dtype), dtype, _halving(12, 12, order), tag="close calls " + order)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_smooth_field_general_m(oracle, dtype):
     rng = np.random.default_rng(77)
