@@ -112,15 +112,6 @@ __device__ __forceinline__ void store_tok(void* p, int bytes, const Tok<NQ, TW>&
     }
 }
 
-// Hides a token's registers from value numbering, so that the rarely taken fp64 code widens the
-// packed words where it uses them instead of keeping fp64 copies of whole tokens alive.
-template <int NQ, int TW>
-__device__ __forceinline__ void forget(Tok<NQ, TW>& t)
-{
-#pragma unroll
-    for (int i = 0; i < Tok<NQ, TW>::N; ++i) asm volatile("" : "+v"(t.w[i]));
-}
-
 // ------------------------------------------------------------------ sums
 // wave64 sum without the LDS crossbar: DPP adds inside each row of 16 lanes, two row broadcasts,
 // and the total (held by lane 63) read back as a wave-uniform value.  One fixed order everywhere.
@@ -168,6 +159,42 @@ template <> __device__ __forceinline__ double elem64<bf16_t>(uint32_t w, int e)
 }
 template <> __device__ __forceinline__ double elem64<float>(uint32_t w, int) { return (double)__uint_as_float(w); }
 
+// wave64 sum of fp64 values, same DPP pattern as wave_total32 applied to both halves of the value
+__device__ __forceinline__ double dpp_move64(double v, const int ctrl_sel)
+{
+    const int lo = __double2loint(v), hi = __double2hiint(v);
+    int xl, xh;
+    switch (ctrl_sel) {
+        case 0: xl = __builtin_amdgcn_update_dpp(0, lo, 0xB1, 0xf, 0xf, false); xh = __builtin_amdgcn_update_dpp(0, hi, 0xB1, 0xf, 0xf, false); break;
+        case 1: xl = __builtin_amdgcn_update_dpp(0, lo, 0x4E, 0xf, 0xf, false); xh = __builtin_amdgcn_update_dpp(0, hi, 0x4E, 0xf, 0xf, false); break;
+        case 2: xl = __builtin_amdgcn_update_dpp(0, lo, 0x141, 0xf, 0xf, false); xh = __builtin_amdgcn_update_dpp(0, hi, 0x141, 0xf, 0xf, false); break;
+        case 3: xl = __builtin_amdgcn_update_dpp(0, lo, 0x140, 0xf, 0xf, false); xh = __builtin_amdgcn_update_dpp(0, hi, 0x140, 0xf, 0xf, false); break;
+        case 4: xl = __builtin_amdgcn_update_dpp(0, lo, 0x142, 0xa, 0xf, false); xh = __builtin_amdgcn_update_dpp(0, hi, 0x142, 0xa, 0xf, false); break;
+        default: xl = __builtin_amdgcn_update_dpp(0, lo, 0x143, 0xc, 0xf, false); xh = __builtin_amdgcn_update_dpp(0, hi, 0x143, 0xc, 0xf, false); break;
+    }
+    return __hiloint2double(xh, xl);
+}
+
+__device__ __forceinline__ double wave_total64(double v)
+{
+    v += dpp_move64(v, 0);
+    v += dpp_move64(v, 1);
+    v += dpp_move64(v, 2);
+    v += dpp_move64(v, 3);
+    v += dpp_move64(v, 4);       // rows the broadcast does not reach add the zero of the disabled lanes
+    v += dpp_move64(v, 5);
+    return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v), 63), __builtin_amdgcn_readlane(__double2loint(v), 63));
+}
+
+// Hides a token's registers from value numbering, so that the rarely taken fp64 code widens the
+// packed words where it uses them instead of keeping fp64 copies of whole tokens alive.
+template <int NQ, int TW>
+__device__ __forceinline__ void forget(Tok<NQ, TW>& t)
+{
+#pragma unroll
+    for (int i = 0; i < Tok<NQ, TW>::N; ++i) asm volatile("" : "+v"(t.w[i]));
+}
+
 // <x, y> in fp64.  The words are widened one at a time (scheduling fences keep the widened copies
 // from piling up in registers: this code runs for a fraction of a percent of the decisions).
 template <typename T, int NQ, int TW>
@@ -182,7 +209,20 @@ __device__ __forceinline__ double dot64(Tok<NQ, TW>& x, Tok<NQ, TW>& y)
         for (int e = 0; e < words<T>::per; ++e) acc = fma(elem64<T>(x.w[i], e), elem64<T>(y.w[i], e), acc);
         __builtin_amdgcn_sched_barrier(0);
     }
-    return wave_sum(acc);
+    return wave_total64(acc);
+}
+
+template <typename T, int NQ, int TW>
+__device__ __forceinline__ double norm64(Tok<NQ, TW>& x) { return dot64<T>(x, x); }
+
+// fp64 squared norms n[p] = <P_p, P_p> and neighbour products d[p] = <P_p, P_p+1> of five tokens that
+// follow each other on a line
+template <typename T, int NQ, int TW>
+__device__ __forceinline__ void chain_sums64(Tok<NQ, TW>& P0, Tok<NQ, TW>& P1, Tok<NQ, TW>& P2, Tok<NQ, TW>& P3, Tok<NQ, TW>& P4,
+                                             double (&n)[5], double (&d)[4])
+{
+    n[0] = norm64<T>(P0); n[1] = norm64<T>(P1); n[2] = norm64<T>(P2); n[3] = norm64<T>(P3); n[4] = norm64<T>(P4);
+    d[0] = dot64<T>(P0, P1); d[1] = dot64<T>(P1, P2); d[2] = dot64<T>(P2, P3); d[3] = dot64<T>(P3, P4);
 }
 
 // 1 / max(|x|, 1e-12) from the squared norm, screening precision (hardware reciprocal square root)
@@ -318,9 +358,14 @@ oim_halve_pair(const T* __restrict__ x, const int32_t* __restrict__ sizes_in, Pa
     const bool active = is_main || is_halo;
     const int r0 = is_halo ? row_base - 4 : row_base + 4 * w;
     const int rr0 = r0 - row_base + 1;                            // LDS index of row r0 (negative only for the halo wave's unused rows)
-    // error bound of a screening cosine: one rounding per word and per reduction step on the dot product,
-    // the same on each squared norm, the reciprocal square roots and two products; two cosines are compared
-    const float tau = (float)(16 * (N * words<T>::per + 8) + 16) * 5.9604645e-8f;
+    // Error bound of the screening, in units of u = 2^-24.  A sum takes at most E = R + 6 roundings of
+    // relative size u on partial sums bounded by the sum of the magnitudes of its terms (R per lane: two
+    // per packed bf16 product pair, one per fp32 product; six reduction steps); against |a||b| that is E u
+    // on a dot product and E u on each squared norm, i.e. (E + 4) u on the two reciprocal norms together
+    // (hardware reciprocal square root: 1 ulp each), plus two products: 2 E + 6 per cosine, 4 E + 13 on
+    // the difference of two.  tau is 1.5 times that.
+    constexpr int kE = N * (words<T>::per == 2 ? 2 : 1) + 6;
+    const float tau = (float)(6 * kE + 20) * 5.9604645e-8f;
     const int tok_bytes = g.D * (int)sizeof(T);
     if (threadIdx.x == 0) redo = 0;
 
@@ -361,17 +406,11 @@ oim_halve_pair(const T* __restrict__ x, const int32_t* __restrict__ sizes_in, Pa
             }
             bool a_left = va > 0, c_left = vc > 0;
             if (va == 0 || vc == 0) {                             // too close for fp32: the fp64 cosines decide
-                const double jb = inv_norm64(dot64<T>(Bt, Bt));
-                if (va == 0) {
-                    const double ja = inv_norm64(dot64<T>(A, A)), jl = inv_norm64(dot64<T>(Lt, Lt));
-                    const double ela = dot64<T>(Lt, A), eab = dot64<T>(A, Bt);
-                    a_left = source_goes_left(true, true, ja, ela, jl, eab, jb);
-                }
-                if (vc == 0) {
-                    const double jc = inv_norm64(dot64<T>(C, C)), jr = inv_norm64(dot64<T>(Rt, Rt));
-                    const double ebc = dot64<T>(Bt, C), ecr = dot64<T>(C, Rt);
-                    c_left = source_goes_left(true, true, jc, ebc, jb, ecr, jr);
-                }
+                double n[5], d[4];
+                chain_sums64<T>(Lt, A, Bt, C, Rt, n, d);
+                const double jb = inv_norm64(n[2]);
+                if (va == 0) a_left = source_goes_left(true, true, inv_norm64(n[1]), d[0], inv_norm64(n[0]), d[1], jb);
+                if (vc == 0) c_left = source_goes_left(true, true, inv_norm64(n[3]), d[2], jb, d[3], inv_norm64(n[4]));
             }
             const bool take_a = !a_left, take_c = has_c && c_left;
             const int sa = take_a ? sa_in : 0, sc = take_c ? sc_in : 0;
@@ -438,13 +477,13 @@ oim_halve_pair(const T* __restrict__ x, const int32_t* __restrict__ sizes_in, Pa
     bool up0 = v0 > 0, up2 = v2 > 0, up4 = v4 > 0;
     if (redo) {                                                   // uniform over the workgroup
         if (active) {
-            const double n0 = dot64<T>(T0, T0), n1 = dot64<T>(T1, T1), n2 = dot64<T>(T2, T2), n3 = dot64<T>(T3, T3);
-            const double d0 = dot64<T>(T0, T1), d1 = dot64<T>(T1, T2), d2 = dot64<T>(T2, T3), d3 = dot64<T>(T3, Tx);
+            double n[5], d[4];
+            chain_sums64<T>(T0, T1, T2, T3, Tx, n, d);
             if (lane < 4) {
                 const int k = lane, r = r0 + k;
                 if (r >= row_lo && r <= row_end) {
-                    inv64[rr0 + k] = inv_norm64(k == 0 ? n0 : k == 1 ? n1 : k == 2 ? n2 : n3);
-                    dt64[rr0 + k] = k == 0 ? d0 : k == 1 ? d1 : k == 2 ? d2 : d3;
+                    inv64[rr0 + k] = inv_norm64(k == 0 ? n[0] : k == 1 ? n[1] : k == 2 ? n[2] : n[3]);
+                    dt64[rr0 + k] = k == 0 ? d[0] : k == 1 ? d[1] : k == 2 ? d[2] : d[3];
                 }
             }
         }
