@@ -117,7 +117,22 @@ def main():
     ms_per_step = wall * 1e3 / args.steps
     tokens_per_s = w.tokens_in / (wall / args.steps)
 
-    # ---- algorithmic bytes: every input element read once, every output element written once
+    # ---- second pass over the same steps with two HIP events around every kernel launch, recorded by the
+    # library on the launch stream (luvc_profile_start): per-kernel durations for the roofline
+    n_prof = min(args.steps, 50)
+    launches_per_step = 16
+    prof = lv.LaunchProfile(n_prof * launches_per_step)
+    prof.start()
+    for i in range(n_prof):
+        step(i)
+    prof.stop()
+    torch.cuda.synchronize()
+    per_kernel = {}
+    for name, ms in prof.results():
+        per_kernel.setdefault(name, []).append(ms)
+    prof.close()
+
+    # ---- algorithmic work per launch: every input element read once, every output element written once
     oim_bytes = 0
     H, W = w.H, w.W
     for passes, out in calls:
@@ -127,27 +142,63 @@ def main():
     score_bytes = w.spu_B * w.spu_N * w.spu_D * es
     prune_bytes = 2 * w.spu_B * w.n_keep * w.spu_D * es
     alg = dict(oim=oim_bytes, spu_score=score_bytes, spu_prune=prune_bytes)
-    names = ["oim", "spu_score", "spu_prune"]
-    kernels = {"oim": "oim_halve x2 per OIM call (W pass, H pass) + map composition", "spu_score": "spu_fft256 (+ tables, finish)",
-               "spu_prune": "spu_select + spu_gather"}
-    dom = int(np.argmax(seg_mean))
-    achieved = alg[names[dom]] / (seg_mean[dom] * 1e-3) / 1e9
-    # HBM bytes per step of the dominant call from the committed rocprofv3 --pmc summary (FETCH_SIZE / WRITE_SIZE,
-    # scaled by the copy-kernel calibration stated there); null when no summary covers this workload
-    traffic = None
+    # per kernel: (algorithmic bytes per step, flops per step or None, roofline that bounds it)
+    L = 2 * w.sigma + 1
+    fft_flops = None
+    if w.spu_N % 256 == 0 and L <= 256:
+        n2 = w.spu_N // 256
+        # per packed channel pair: N2 forward + N2 inverse 256-point transforms (5 P log2 P each), the
+        # pass-band accumulation and expansion (8 flops per bin and subsequence, both ways), the energy
+        fft_flops = w.spu_B * (w.spu_D / 2) * (2 * n2 * 5 * 256 * 8 + 2 * 8 * n2 * L + 4 * w.spu_N)
+    work = {
+        "oim_halve_pair": (oim_bytes, None, "hbm"), "oim_halve": (oim_bytes, None, "hbm"),
+        "spu_fft256": (score_bytes, fft_flops, "alu"),
+        "spu_fwd_dense": (score_bytes, None, "hbm"),
+        "spu_gather": (prune_bytes, None, "hbm"),
+    }
     try:
         with open(os.path.join(ROOT, "profiles", "hbm_traffic.json")) as f:
-            t = json.load(f)[w.name][names[dom]]
-        traffic = {"read_bytes": t["read_bytes"], "write_bytes": t["write_bytes"], "total_bytes": t["read_bytes"] + t["write_bytes"]}
-    except (OSError, KeyError, ValueError):
-        pass
-    roofline = {"bound": "hbm", "kernel": kernels[names[dom]], "call": names[dom], "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
-                "algorithmic_bytes": alg[names[dom]], "avg_ms": round(float(seg_mean[dom]), 5),
-                "whole_step": {"algorithmic_bytes": sum(alg.values()),
-                               "achieved": round(sum(alg.values()) / (ms_per_step * 1e-3) / 1e9, 1),
-                               "frac": round(sum(alg.values()) / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
-                "segments_ms": {n: round(float(v), 5) for n, v in zip(names, seg_mean)}}
+            measured_traffic = json.load(f).get(w.name, {})
+    except (OSError, ValueError):
+        measured_traffic = {}
+    kernels = []
+    for name, v in per_kernel.items():
+        per_step = len(v) / n_prof
+        avg_ms = float(np.mean(v))
+        k = {"kernel": name, "launches_per_step": round(per_step, 2), "avg_us": round(avg_ms * 1e3, 2),
+             "us_per_step": round(avg_ms * 1e3 * per_step, 2)}
+        if name in work:
+            by, fl, bound = work[name]
+            k["bound"] = bound
+            k["algorithmic_bytes_per_launch"] = int(by / per_step)
+            k["hbm_GBps"] = round(by / per_step / (avg_ms * 1e-3) / 1e9, 1)
+            k["hbm_frac"] = round(k["hbm_GBps"] / HBM_PEAK_GBS, 4)
+            if fl:
+                k["algorithmic_flops_per_launch"] = int(fl / per_step)
+                k["TFLOPs"] = round(fl / per_step / (avg_ms * 1e-3) / 1e12, 2)
+        t = measured_traffic.get(name)
+        if t:
+            k["traffic_bytes_per_launch"] = int(t["read_bytes"] + t["write_bytes"])
+        kernels.append(k)
+    kernels.sort(key=lambda k: -k["us_per_step"])
+    dom = kernels[0]
+    if dom.get("bound") == "alu":
+        # fp32 vector peak of MI355X: 256 CUs x 4 SIMDs x 16 lanes x 2 (packed) x 2 flops x 2.4 GHz
+        roofline = {"bound": "alu", "kernel": dom["kernel"], "achieved": dom["TFLOPs"], "peak": 157.3, "unit": "TFLOP/s",
+                    "frac": round(dom["TFLOPs"] / 157.3, 4), "traffic": dom.get("traffic_bytes_per_launch"),
+                    "avg_us": dom["avg_us"], "algorithmic_flops": dom["algorithmic_flops_per_launch"],
+                    "hbm_view": {"achieved": dom["hbm_GBps"], "peak": HBM_PEAK_GBS, "frac": dom["hbm_frac"],
+                                 "algorithmic_bytes": dom["algorithmic_bytes_per_launch"]}}
+    else:
+        roofline = {"bound": "hbm", "kernel": dom["kernel"], "achieved": dom.get("hbm_GBps"), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": dom.get("hbm_frac"), "traffic": dom.get("traffic_bytes_per_launch"), "avg_us": dom["avg_us"],
+                    "algorithmic_bytes": dom.get("algorithmic_bytes_per_launch")}
+    roofline["timing"] = f"start/stop HIP events attached by the library to every dispatch on the launch stream, {n_prof} steps after the timed region"
+    roofline["kernels"] = kernels
+    roofline["whole_step"] = {"algorithmic_bytes": sum(alg.values()),
+                              "achieved": round(sum(alg.values()) / (ms_per_step * 1e-3) / 1e9, 1),
+                              "frac": round(sum(alg.values()) / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+    roofline["calls_ms"] = {n: round(float(v), 5) for n, v in zip(["oim", "spu_score", "spu_prune"], seg_mean)}
 
     result = {
         "metric": "visual tokens compressed/sec (OIM+SPU)", "value": round(tokens_per_s, 1), "unit": "tokens/s",
@@ -170,7 +221,7 @@ def cpu_baseline(w, x_oim_host, x_spu_host):
     import oracle
     from paper_2512_09010_amd import workloads as wl
 
-    n_s = min(w.spu_B, 8)                                   # SPU samples (each an independent OpenMP job)
+    n_s = min(w.spu_B, 16)                                  # SPU samples (each an independent OpenMP job)
     frac = n_s / w.spu_B
     n_g = max(1, int(round(w.grids * frac)))
     rm = oracle.ROUND_BF16 if w.dtype == "bf16" else oracle.ROUND_F32

@@ -151,6 +151,25 @@ luvc_status luvc_spu_prune(const void* x, const float* scores, int B, int N, int
                            luvc_dtype dtype, int n_keep, int32_t* kept_idx, void* x_out,
                            void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/*
+ * Timing aid for benchmarks (not a step of the paper's method; for callers that want the duration of
+ * each kernel the library launches, measured on the launch stream itself).
+ *
+ *   hip_events  host array of n_events hipEvent_t handles created by the caller with timing enabled
+ *               (n_events even, >= 2); the caller keeps ownership and must keep them alive until
+ *               luvc_profile_stop()
+ * From luvc_profile_start() until luvc_profile_stop(), on the calling thread, every kernel launched by
+ * a luvc_* call carries events[2i] as its start and events[2i+1] as its stop event (attached to the dispatch
+ * itself, so hipEventElapsedTime of the pair is the kernel's run time on the device), i = 0, 1, ... in
+ * launch order; launches beyond n_events / 2 (or 8192) are not recorded.
+ * luvc_profile_stop() ends the recording and returns the number of launches recorded;
+ * luvc_profile_kernel(i) names the kernel of launch i of the last recording (static string).
+ * Timed launches are dispatched one by one: do not leave it on in production.
+ */
+luvc_status luvc_profile_start(void** hip_events, int n_events);
+int luvc_profile_stop(void);
+const char* luvc_profile_kernel(int i);
+
 #ifdef __cplusplus
 }
 #endif

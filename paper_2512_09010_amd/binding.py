@@ -17,7 +17,8 @@ LUVC_OK, LUVC_ERR_INVALID_ARG, LUVC_ERR_UNSUPPORTED, LUVC_ERR_WORKSPACE, LUVC_ER
 LUVC_F32, LUVC_BF16 = 0, 1
 
 EXPORTS = ("luvc_version", "luvc_last_error", "luvc_oim_plan", "luvc_oim_workspace_bytes", "luvc_oim_merge",
-           "luvc_spu_workspace_bytes", "luvc_spu_score", "luvc_keep_count", "luvc_spu_prune")
+           "luvc_spu_workspace_bytes", "luvc_spu_score", "luvc_keep_count", "luvc_spu_prune",
+           "luvc_profile_start", "luvc_profile_stop", "luvc_profile_kernel")
 
 
 class LuvcPass(ctypes.Structure):
@@ -60,6 +61,12 @@ def lib() -> ctypes.CDLL:
     L.luvc_keep_count.restype = i
     L.luvc_spu_prune.argtypes = [vp, vp, i, i, i, i64, i, i, vp, vp, vp, sz, vp]
     L.luvc_spu_prune.restype = i
+    L.luvc_profile_start.argtypes = [ctypes.POINTER(vp), i]
+    L.luvc_profile_start.restype = i
+    L.luvc_profile_stop.argtypes = []
+    L.luvc_profile_stop.restype = i
+    L.luvc_profile_kernel.argtypes = [i]
+    L.luvc_profile_kernel.restype = ctypes.c_char_p
     _lib = L
     return L
 
@@ -189,3 +196,48 @@ def luvc_spu_prune(x, scores, n_keep: int, gather: bool = True, stream=None, out
     _check(lib().luvc_spu_prune(xp, _ptr(scores), B, N, D, stride, code, int(n_keep), _ptr(out["kept_idx"]),
                                 _ptr(out.get("x")), None, 0, _stream(stream)))
     return out
+
+
+class LaunchProfile:
+    """Durations of the kernels libluvc launches between start() and stop(), from HIP events recorded on
+    the launch stream (luvc_profile_start / luvc_profile_stop).  Only marshals: the events come from the
+    HIP runtime, the recording is done by the library."""
+
+    def __init__(self, max_launches: int):
+        self._hip = ctypes.CDLL("libamdhip64.so")
+        self._hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self._hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self._hip.hipEventSynchronize.argtypes = [ctypes.c_void_p]
+        self._hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+        self.n = 2 * int(max_launches)
+        self.events = (ctypes.c_void_p * self.n)()
+        for k in range(self.n):
+            e = ctypes.c_void_p()
+            if self._hip.hipEventCreate(ctypes.byref(e)) != 0:
+                raise RuntimeError("hipEventCreate failed")
+            self.events[k] = e
+        self.count = 0
+
+    def start(self):
+        _check(lib().luvc_profile_start(self.events, self.n))
+
+    def stop(self) -> int:
+        self.count = lib().luvc_profile_stop()
+        return self.count
+
+    def results(self):
+        """[(kernel name, milliseconds)] in launch order; call after the stream has been synchronised."""
+        out = []
+        for k in range(self.count):
+            ms = ctypes.c_float(0)
+            self._hip.hipEventSynchronize(self.events[2 * k + 1])
+            if self._hip.hipEventElapsedTime(ctypes.byref(ms), self.events[2 * k], self.events[2 * k + 1]) != 0:
+                raise RuntimeError("hipEventElapsedTime failed")
+            out.append((lib().luvc_profile_kernel(k).decode(), float(ms.value)))
+        return out
+
+    def close(self):
+        for k in range(self.n):
+            if self.events[k]:
+                self._hip.hipEventDestroy(self.events[k])
+                self.events[k] = None

@@ -31,6 +31,22 @@ luvc_status check_launch(const char* what)
     return LUVC_OK;
 }
 
+// ---- timing aid: events handed over by the caller, two per launch
+static thread_local hipEvent_t* g_prof_ev = nullptr;
+static thread_local int g_prof_cap = 0, g_prof_n = 0;
+constexpr int kProfMax = 8192;
+static thread_local const char* g_prof_name[kProfMax];
+
+bool prof_take(const char* kernel, hipEvent_t* start, hipEvent_t* stop)
+{
+    if (!g_prof_ev || g_prof_n >= g_prof_cap || g_prof_n >= kProfMax) return false;
+    const int slot = g_prof_n++;
+    g_prof_name[slot] = kernel;
+    *start = g_prof_ev[2 * slot];
+    *stop = g_prof_ev[2 * slot + 1];
+    return true;
+}
+
 static bool dtype_ok(luvc_dtype dt) { return dt == LUVC_F32 || dt == LUVC_BF16; }
 static size_t esize(luvc_dtype dt) { return dt == LUVC_F32 ? 4 : 2; }
 
@@ -115,6 +131,25 @@ extern "C" {
 const char* luvc_version(void) { return "libluvc 0.1 (gfx950)"; }
 
 const char* luvc_last_error(void) { return g_err; }
+
+luvc_status luvc_profile_start(void** hip_events, int n_events)
+{
+    if (!hip_events || n_events < 2 || (n_events & 1)) { set_error("luvc_profile_start needs an even number of events"); return LUVC_ERR_INVALID_ARG; }
+    g_prof_ev = reinterpret_cast<hipEvent_t*>(hip_events);
+    g_prof_cap = n_events / 2;
+    g_prof_n = 0;
+    return LUVC_OK;
+}
+
+int luvc_profile_stop(void)
+{
+    const int n = g_prof_n;
+    g_prof_ev = nullptr;
+    g_prof_cap = 0;
+    return n;
+}
+
+const char* luvc_profile_kernel(int i) { return (i >= 0 && i < g_prof_n) ? g_prof_name[i] : ""; }
 
 luvc_status luvc_oim_plan(int H, int W, int64_t target_tokens, luvc_oim_pass* passes, int max_passes, int* n_passes)
 {

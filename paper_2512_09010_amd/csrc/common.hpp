@@ -2,6 +2,7 @@
 // reductions, error plumbing.  Nothing here is shared with the CPU oracle.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include "../../include/luvc.h"
@@ -13,6 +14,21 @@ constexpr int kWave = 64;
 // ------------------------------------------------------------------ host-side error text
 void set_error(const char* fmt, ...);
 luvc_status check_launch(const char* what);
+
+// ------------------------------------------------------------------ optional timing of the library's launches
+// While a caller has installed a list of events (luvc_profile_start), every launch goes out with a
+// start and a stop event attached to the dispatch itself, so their difference is the kernel's own
+// run time on the device.  prof_take() hands out the next pair (or returns false).
+bool prof_take(const char* kernel, hipEvent_t* start, hipEvent_t* stop);
+
+#define LUVC_LAUNCH(NAME, KERNEL, GRID, BLOCK, LDS, ST, ...)                                              \
+    do {                                                                                                  \
+        hipEvent_t e0_, e1_;                                                                              \
+        if (::luvc::prof_take(NAME, &e0_, &e1_))                                                          \
+            hipExtLaunchKernelGGL(KERNEL, GRID, BLOCK, LDS, ST, e0_, e1_, 0, __VA_ARGS__);                \
+        else                                                                                              \
+            hipLaunchKernelGGL(KERNEL, GRID, BLOCK, LDS, ST, __VA_ARGS__);                                \
+    } while (0)
 
 static inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 

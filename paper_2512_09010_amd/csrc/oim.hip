@@ -249,15 +249,15 @@ static luvc_status run_pass(const T* x, const int32_t* sizes_in, int B, int H, i
     const int Ho = axis ? H : H - m, Wo = axis ? W - m : W;
     const int64_t n_out = (int64_t)B * Ho * Wo;
     const unsigned g1 = (unsigned)((n_tok * 64 + 255) / 256);
-    if (vec) hipLaunchKernelGGL((oim_pairdot<T, true>), dim3(g1), dim3(256), 0, st, x, ws.n2, ws.dn, n_tok, H, W, D, axis);
-    else     hipLaunchKernelGGL((oim_pairdot<T, false>), dim3(g1), dim3(256), 0, st, x, ws.n2, ws.dn, n_tok, H, W, D, axis);
+    if (vec) LUVC_LAUNCH("oim_pairdot", (oim_pairdot<T, true>), dim3(g1), dim3(256), 0, st, x, ws.n2, ws.dn, n_tok, H, W, D, axis);
+    else     LUVC_LAUNCH("oim_pairdot", (oim_pairdot<T, false>), dim3(g1), dim3(256), 0, st, x, ws.n2, ws.dn, n_tok, H, W, D, axis);
     const size_t lds = sizeof(double) * n_src + sizeof(int) * n_src + sizeof(int) * (256 + 1) + (size_t)len + 16;
-    hipLaunchKernelGGL(oim_decide, dim3((unsigned)(B * nlines)), dim3(256), lds, st, ws.n2, ws.dn, H, W, axis, m,
+    LUVC_LAUNCH("oim_decide", oim_decide, dim3((unsigned)(B * nlines)), dim3(256), lds, st, ws.n2, ws.dn, H, W, axis, m,
                        pass_map, ws.anchor, ws.absorb);
     const unsigned g3 = (unsigned)((n_out * 64 + 255) / 256);
-    if (vec) hipLaunchKernelGGL((oim_merge<T, true>), dim3(g3), dim3(256), 0, st, x, sizes_in, ws.anchor, ws.absorb, kept_prev,
+    if (vec) LUVC_LAUNCH("oim_merge", (oim_merge<T, true>), dim3(g3), dim3(256), 0, st, x, sizes_in, ws.anchor, ws.absorb, kept_prev,
                                 n_out, H * W, Ho * Wo, W, D, axis, x_out, sizes_out, kept_out);
-    else     hipLaunchKernelGGL((oim_merge<T, false>), dim3(g3), dim3(256), 0, st, x, sizes_in, ws.anchor, ws.absorb, kept_prev,
+    else     LUVC_LAUNCH("oim_merge", (oim_merge<T, false>), dim3(g3), dim3(256), 0, st, x, sizes_in, ws.anchor, ws.absorb, kept_prev,
                                 n_out, H * W, Ho * Wo, W, D, axis, x_out, sizes_out, kept_out);
     return check_launch("oim pass");
 }
@@ -281,7 +281,7 @@ luvc_status oim_compose(const int32_t* const* maps, const int32_t* n_in, int n, 
     pm.n = n;
     for (int i = 0; i < n; ++i) { pm.map[i] = maps[i]; pm.n_in[i] = n_in[i]; }
     const int64_t total = (int64_t)B * n_first;
-    hipLaunchKernelGGL(oim_compose_merged, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, pm, total, n_first,
+    LUVC_LAUNCH("oim_compose_merged", oim_compose_merged, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, pm, total, n_first,
                        merged_out);
     return check_launch("oim compose");
 }

@@ -234,7 +234,7 @@ static void launch_halve(const T* x, const int32_t* sizes_in, int B, int H, int 
     const int cap = tune < 1 ? 1 : (tune > 8 ? 8 : tune);
     const int spt = nd < cap ? nd : cap;                   // wavefronts (= output slots) per workgroup
     const int tiles = (nd + spt - 1) / spt;
-    hipLaunchKernelGGL((oim_halve<T, NCH>), dim3((unsigned)((int64_t)B * nlines * tiles)), dim3(64 * spt), 0, st,
+    LUVC_LAUNCH("oim_halve", (oim_halve<T, NCH>), dim3((unsigned)((int64_t)B * nlines * tiles)), dim3(64 * spt), 0, st,
                        x, sizes_in, H, W, D, axis, tiles, spt, kept_prev, x_out, sizes_out, pass_map, kept_out);
 }
 

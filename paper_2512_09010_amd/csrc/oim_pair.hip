@@ -601,7 +601,7 @@ luvc_status launch_pair(const T* x, const int32_t* sizes_in, int B, int H, int W
     g.segs = p.segs;
     g.seg_out = p.seg_out;
     const size_t lds = (size_t)p.waves * N * 64 * 4;           // at most 16 * 10 * 256 = 40 KiB
-    hipLaunchKernelGGL((oim_halve_pair<T, NQ, TW, NW>), dim3((unsigned)((int64_t)B * g.segs * g.nd1)), dim3(64 * p.waves), lds, st,
+    LUVC_LAUNCH("oim_halve_pair", (oim_halve_pair<T, NQ, TW, NW>), dim3((unsigned)((int64_t)B * g.segs * g.nd1)), dim3(64 * p.waves), lds, st,
                        x, sizes_in, g, kept_prev, x_out, sizes_out, pair_map, kept_out);
     return check_launch("oim halving pair");
 }

@@ -254,7 +254,7 @@ luvc_status spu_score_fft(const void* x, int B, int N, int D, int64_t row_stride
     // channel pairs are fetched with one access when every pair is naturally aligned
     const size_t pair_bytes = dt == LUVC_F32 ? 8 : 4;
     const bool aligned = (row_stride % 2 == 0) && ((uintptr_t)x % pair_bytes == 0) && (D % 2 == 0);
-#define LUVC_FFT(TT, P2, AL) hipLaunchKernelGGL((spu_fft256<TT, P2, AL>), grid, dim3(256), lds, st, (const TT*)x, N, D, row_stride, sigma, tw, gm, partial)
+#define LUVC_FFT(TT, P2, AL) LUVC_LAUNCH("spu_fft256", (spu_fft256<TT, P2, AL>), grid, dim3(256), lds, st, (const TT*)x, N, D, row_stride, sigma, tw, gm, partial)
 #define LUVC_FFT_T(TT) do { if (pow2) { if (aligned) LUVC_FFT(TT, true, true); else LUVC_FFT(TT, true, false); } \
                             else { if (aligned) LUVC_FFT(TT, false, true); else LUVC_FFT(TT, false, false); } } while (0)
     if (dt == LUVC_F32) LUVC_FFT_T(float); else LUVC_FFT_T(bf16_t);

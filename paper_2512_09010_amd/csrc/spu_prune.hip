@@ -151,18 +151,18 @@ spu_gather(const unsigned char* __restrict__ x, const int32_t* __restrict__ kept
 luvc_status spu_prune_run(const void* x, const float* scores, int B, int N, int D, int64_t row_stride, luvc_dtype dt,
                           int n_keep, int32_t* kept_idx, void* x_out, hipStream_t st)
 {
-    hipLaunchKernelGGL(spu_select, dim3((unsigned)B), dim3(kSelThreads), 0, st, scores, N, n_keep, kept_idx);
+    LUVC_LAUNCH("spu_select", spu_select, dim3((unsigned)B), dim3(kSelThreads), 0, st, scores, N, n_keep, kept_idx);
     if (x_out) {
         const int es = dt == LUVC_F32 ? 4 : 2;
         const int64_t rin = row_stride * es, rout = (int64_t)D * es, rows = (int64_t)B * n_keep;
         const unsigned g = (unsigned)((rows * 64 + 255) / 256);
         const bool v16 = rin % 16 == 0 && rout % 16 == 0 && ((uintptr_t)x % 16 == 0) && ((uintptr_t)x_out % 16 == 0);
         if (v16)
-            hipLaunchKernelGGL((spu_gather<16>), dim3(g), dim3(256), 0, st, (const unsigned char*)x, kept_idx, N, n_keep, rin, rout, rows, (unsigned char*)x_out);
+            LUVC_LAUNCH("spu_gather", (spu_gather<16>), dim3(g), dim3(256), 0, st, (const unsigned char*)x, kept_idx, N, n_keep, rin, rout, rows, (unsigned char*)x_out);
         else if (es == 4)
-            hipLaunchKernelGGL((spu_gather<4>), dim3(g), dim3(256), 0, st, (const unsigned char*)x, kept_idx, N, n_keep, rin, rout, rows, (unsigned char*)x_out);
+            LUVC_LAUNCH("spu_gather", (spu_gather<4>), dim3(g), dim3(256), 0, st, (const unsigned char*)x, kept_idx, N, n_keep, rin, rout, rows, (unsigned char*)x_out);
         else
-            hipLaunchKernelGGL((spu_gather<2>), dim3(g), dim3(256), 0, st, (const unsigned char*)x, kept_idx, N, n_keep, rin, rout, rows, (unsigned char*)x_out);
+            LUVC_LAUNCH("spu_gather", (spu_gather<2>), dim3(g), dim3(256), 0, st, (const unsigned char*)x, kept_idx, N, n_keep, rin, rout, rows, (unsigned char*)x_out);
     }
     return check_launch("spu prune");
 }

@@ -174,22 +174,22 @@ luvc_status spu_score_dense(const void* x, int B, int N, int D, int64_t row_stri
     float* Fc = (float*)(ws + L.Fc);
     float* Fs = (float*)(ws + L.Fs);
     float* partial = (float*)(ws + L.partial);
-    hipLaunchKernelGGL(spu_tables, dim3((unsigned)((N + 255) / 256)), dim3(256), 0, st, N, sigma, use_hamming, tw, gk, gm);
+    LUVC_LAUNCH("spu_tables", spu_tables, dim3((unsigned)((N + 255) / 256)), dim3(256), 0, st, N, sigma, use_hamming, tw, gk, gm);
     const int64_t total = (int64_t)B * N;
     if (L.fast) {
         const luvc_status rc = spu_score_fft(x, B, N, D, row_stride, dt, sigma, tw, gm, partial, L.n_tiles, st);
         if (rc != LUVC_OK) return rc;
-        hipLaunchKernelGGL(spu_finish, dim3((unsigned)((total + 63) / 64)), dim3(64 * kFinParts), 0, st, partial, N, L.n_tiles, total, scores);
+        LUVC_LAUNCH("spu_finish", spu_finish, dim3((unsigned)((total + 63) / 64)), dim3(64 * kFinParts), 0, st, partial, N, L.n_tiles, total, scores);
         return check_launch("spu score");
     }
     const dim3 gf((unsigned)L.n_tiles, (unsigned)((sigma + 1 + 4 * kKPW - 1) / (4 * kKPW)), (unsigned)B);
     if (dt == LUVC_F32)
-        hipLaunchKernelGGL((spu_fwd_dense<float>), gf, dim3(256), 0, st, (const float*)x, N, D, row_stride, sigma, tw, Fc, Fs);
+        LUVC_LAUNCH("spu_fwd_dense", (spu_fwd_dense<float>), gf, dim3(256), 0, st, (const float*)x, N, D, row_stride, sigma, tw, Fc, Fs);
     else
-        hipLaunchKernelGGL((spu_fwd_dense<bf16_t>), gf, dim3(256), 0, st, (const bf16_t*)x, N, D, row_stride, sigma, tw, Fc, Fs);
+        LUVC_LAUNCH("spu_fwd_dense", (spu_fwd_dense<bf16_t>), gf, dim3(256), 0, st, (const bf16_t*)x, N, D, row_stride, sigma, tw, Fc, Fs);
     const dim3 gi((unsigned)L.n_tiles, (unsigned)((N + kNChunk - 1) / kNChunk), (unsigned)B);
-    hipLaunchKernelGGL(spu_inv_dense, gi, dim3(256), 0, st, Fc, Fs, N, D, sigma, tw, gk, partial);
-    hipLaunchKernelGGL(spu_finish, dim3((unsigned)((total + 63) / 64)), dim3(64 * kFinParts), 0, st, partial, N, L.n_tiles, total, scores);
+    LUVC_LAUNCH("spu_inv_dense", spu_inv_dense, gi, dim3(256), 0, st, Fc, Fs, N, D, sigma, tw, gk, partial);
+    LUVC_LAUNCH("spu_finish", spu_finish, dim3((unsigned)((total + 63) / 64)), dim3(64 * kFinParts), 0, st, partial, N, L.n_tiles, total, scores);
     return check_launch("spu score");
 }
 

@@ -108,6 +108,20 @@ def test_pair_without_maps(oracle):
     np.testing.assert_array_equal(out["sizes"].cpu().numpy().astype(np.int64), ref["sizes"])
 
 
+def test_pair_tiny_values(oracle):
+    # a sprinkle of values around and below the smallest normal bf16 / fp32-exact magnitudes: merged
+    # results in the subnormal range must still be the correctly rounded ones
+    rng = np.random.default_rng(17)
+    x = wl.smooth_field(rng, 1, 8, 8, 256, 2.0)
+    tiny = rng.random(x.shape) < 0.05
+    x[tiny] *= np.float32(1e-38)
+    x[rng.random(x.shape) < 0.01] = 0.0
+    sizes = rng.integers(1, 4, (1, 8, 8))
+    for dtype in ("bf16", "f32"):
+        run_case(oracle, wl.cast_io(x, dtype), dtype, _halving(8, 8, "WH"), tag="tiny values")
+        run_case(oracle, wl.cast_io(x, dtype), dtype, _halving(8, 8, "WH"), sizes=sizes, tag="tiny values+sizes")
+
+
 def test_pair_close_calls(oracle):
     # rows of near-duplicate tokens: most cosines differ by less than the fp32 screening bound, so the
     # fp64 repeat of both passes decides; exact duplicates tie and go to the lower position
