@@ -141,6 +141,58 @@ template <> __device__ __forceinline__ float dot_word<float>(float acc, uint32_t
     return fmaf(__uint_as_float(x), __uint_as_float(y), acc);
 }
 
+// Eight wave64 sums at once.  Three exchange steps inside a quad / half row keep, in every lane, only
+// the partial sum of value (lane & 7): each step halves the number of registers instead of adding every
+// value in every lane.  Then one add across the half rows, one across the two halves of the wave
+// and one across neighbouring rows (lane-swap instructions), and lane i holds the total of value i.
+// Six additions per term, like the one-value sum above.
+__device__ __forceinline__ float dpp_get(float v, const int sel)
+{
+    const int x = __float_as_int(v);
+    switch (sel) {
+        case 0: return __int_as_float(__builtin_amdgcn_update_dpp(0, x, 0xB1, 0xf, 0xf, true));    // quad_perm [1,0,3,2]: lane ^ 1
+        case 1: return __int_as_float(__builtin_amdgcn_update_dpp(0, x, 0x4E, 0xf, 0xf, true));    // quad_perm [2,3,0,1]: lane ^ 2
+        case 2: return __int_as_float(__builtin_amdgcn_update_dpp(0, x, 0x141, 0xf, 0xf, true));   // row_half_mirror: lane ^ 7
+        case 3: return __int_as_float(__builtin_amdgcn_update_dpp(0, x, 0x1B, 0xf, 0xf, true));    // quad_perm [3,2,1,0]: lane ^ 3
+        default: return __int_as_float(__builtin_amdgcn_update_dpp(0, x, 0x128, 0xf, 0xf, true));  // row_ror:8: lane ^ 8
+    }
+}
+
+__device__ __forceinline__ void wave_total32x8(float (&v)[8], int lane)
+{
+    const bool b0 = lane & 1, b1 = lane & 2, b2 = lane & 4;
+    float p[4], q[2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const float keep = b0 ? v[2 * i + 1] : v[2 * i], send = b0 ? v[2 * i] : v[2 * i + 1];
+        p[i] = keep + dpp_get(send, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const float keep = b1 ? p[2 * i + 1] : p[2 * i], send = b1 ? p[2 * i] : p[2 * i + 1];
+        q[i] = keep + dpp_get(send, 1);
+    }
+    const float keep = b2 ? q[1] : q[0], send = b2 ? q[0] : q[1];
+    float r = keep + dpp_get(dpp_get(send, 2), 3);                  // (lane ^ 7) ^ 3 = lane ^ 4
+    r += dpp_get(r, 4);
+    const auto h = __builtin_amdgcn_permlane32_swap(__float_as_uint(r), __float_as_uint(r), false, false);
+    r = __uint_as_float(h[0]) + __uint_as_float(h[1]);
+    const auto g = __builtin_amdgcn_permlane16_swap(__float_as_uint(r), __float_as_uint(r), false, false);
+    r = __uint_as_float(g[0]) + __uint_as_float(g[1]);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(r), i));
+}
+
+// this lane's part of <x, y>
+template <typename T, int NQ, int TW>
+__device__ __forceinline__ float dot32_lane(const Tok<NQ, TW>& x, const Tok<NQ, TW>& y)
+{
+    float acc = 0.f;
+#pragma unroll
+    for (int i = 0; i < Tok<NQ, TW>::N; ++i) acc = dot_word<T>(acc, x.w[i], y.w[i]);
+    return acc;
+}
+
 // screening sum <x, y> in fp32 (wave-uniform result)
 template <typename T, int NQ, int TW>
 __device__ __forceinline__ float dot32(const Tok<NQ, TW>& x, const Tok<NQ, TW>& y)
@@ -263,9 +315,22 @@ __device__ __forceinline__ bool source_goes_left(bool has_left, bool has_right, 
 
 // ------------------------------------------------------------------ merge
 template <typename T> __device__ __forceinline__ uint32_t pack_word(double q0, double q1);
+// fp64 -> bf16 with one nearest-even rounding: Veltkamp's splitting with the constant 2^45 + 1 leaves
+// the 8 leading bits of q, rounded to nearest even (the product and the two differences each round
+// once, and their errors cancel exactly); that value is exact in fp32, whose upper half is the bf16.
+// The hardware conversion takes it from there, which only matters below the smallest normal bf16
+// (2^-126), where it rounds the 8-bit value once more onto the subnormal grid.
 template <> __device__ __forceinline__ uint32_t pack_word<bf16_t>(double q0, double q1)
 {
-    return (uint32_t)f64_to_bf16(q0) | ((uint32_t)f64_to_bf16(q1) << 16);
+    const double c = 35184372088833.0;            // 2^45 + 1
+    const double g0 = c * q0, g1 = c * q1;
+    f32x2_t v;
+    v[0] = (float)(g0 + (q0 - g0));
+    v[1] = (float)(g1 + (q1 - g1));
+    const bf16x2_t r = __builtin_convertvector(v, bf16x2_t);
+    uint32_t u;
+    __builtin_memcpy(&u, &r, 4);
+    return u;
 }
 template <> __device__ __forceinline__ uint32_t pack_word<float>(double q0, double) { return __float_as_uint((float)q0); }
 
@@ -395,14 +460,16 @@ oim_halve_pair(const T* __restrict__ x, const int32_t* __restrict__ sizes_in, Pa
             const int sa_in = sizes_in ? sizes_in[ta] : 1;
             const int sc_in = (sizes_in && has_c) ? sizes_in[tc] : 1;
             // screening: every sum is formed lower position first, so the sum two workgroups share has the same bits
-            const float ia = inv_norm32(dot32<T>(A, A)), ib = inv_norm32(dot32<T>(Bt, Bt));
-            const float dab = dot32<T>(A, Bt);
+            // (tokens that are not there were loaded as zeros: their sums are zero and never looked at)
+            float sm[8] = {dot32_lane<T>(A, A), dot32_lane<T>(Bt, Bt), dot32_lane<T>(A, Bt), dot32_lane<T>(Lt, A),
+                           dot32_lane<T>(Lt, Lt), dot32_lane<T>(C, C), dot32_lane<T>(Bt, C), dot32_lane<T>(C, Rt)};
+            wave_total32x8(sm, lane);
+            const float ia = inv_norm32(sm[0]), ib = inv_norm32(sm[1]), dab = sm[2];
             int va = -1, vc = -1;
-            if (has_l) va = screen_source(true, true, ia, dot32<T>(Lt, A), inv_norm32(dot32<T>(Lt, Lt)), dab, ib, tau);
+            if (has_l) va = screen_source(true, true, ia, sm[3], inv_norm32(sm[4]), dab, ib, tau);
             if (has_c) {
                 vc = 1;
-                if (has_r) vc = screen_source(true, true, inv_norm32(dot32<T>(C, C)), dot32<T>(Bt, C), ib,
-                                              dot32<T>(C, Rt), inv_norm32(dot32<T>(Rt, Rt)), tau);
+                if (has_r) vc = screen_source(true, true, inv_norm32(sm[5]), sm[6], ib, sm[7], inv_norm32(dot32<T>(Rt, Rt)), tau);
             }
             bool a_left = va > 0, c_left = vc > 0;
             if (va == 0 || vc == 0) {                             // too close for fp32: the fp64 cosines decide
@@ -442,8 +509,10 @@ oim_halve_pair(const T* __restrict__ x, const int32_t* __restrict__ sizes_in, Pa
         zero_tok(Tx);
     }
     if (active) {
-        const float n0 = dot32<T>(T0, T0), n1 = dot32<T>(T1, T1), n2 = dot32<T>(T2, T2), n3 = dot32<T>(T3, T3);
-        const float d0 = dot32<T>(T0, T1), d1 = dot32<T>(T1, T2), d2 = dot32<T>(T2, T3), d3 = dot32<T>(T3, Tx);
+        float sm[8] = {dot32_lane<T>(T0, T0), dot32_lane<T>(T1, T1), dot32_lane<T>(T2, T2), dot32_lane<T>(T3, T3),
+                       dot32_lane<T>(T0, T1), dot32_lane<T>(T1, T2), dot32_lane<T>(T2, T3), dot32_lane<T>(T3, Tx)};
+        wave_total32x8(sm, lane);
+        const float n0 = sm[0], n1 = sm[1], n2 = sm[2], n3 = sm[3], d0 = sm[4], d1 = sm[5], d2 = sm[6], d3 = sm[7];
         if (lane < 4) {
             const int k = lane, r = r0 + k;
             if (r >= row_lo && r <= row_end) {
