@@ -145,14 +145,15 @@ def main():
     # per kernel: (algorithmic bytes per step, flops per step or None, roofline that bounds it)
     L = 2 * w.sigma + 1
     fft_flops = None
-    if w.spu_N % 256 == 0 and L <= 256:
-        n2 = w.spu_N // 256
-        # per packed channel pair: N2 forward + N2 inverse 256-point transforms (5 P log2 P each), the
+    n1 = next((16 * q for q in (16, 15, 9) if w.spu_N % (16 * q) == 0 and L <= 16 * q), None)
+    if n1 and w.spu_N <= 4096:
+        n2 = w.spu_N // n1
+        # per packed channel pair: N2 forward + N2 inverse N1-point transforms (5 P log2 P each), the
         # pass-band accumulation and expansion (8 flops per bin and subsequence, both ways), the energy
-        fft_flops = w.spu_B * (w.spu_D / 2) * (2 * n2 * 5 * 256 * 8 + 2 * 8 * n2 * L + 4 * w.spu_N)
+        fft_flops = w.spu_B * (w.spu_D / 2) * (2 * n2 * 5 * n1 * np.log2(n1) + 2 * 8 * n2 * L + 4 * w.spu_N)
     work = {
         "oim_halve_pair": (oim_bytes, None, "hbm"), "oim_halve": (oim_bytes, None, "hbm"),
-        "spu_fft256": (score_bytes, fft_flops, "alu"),
+        "spu_fft": (score_bytes, fft_flops, "alu"),
         "spu_fwd_dense": (score_bytes, None, "hbm"),
         "spu_gather": (prune_bytes, None, "hbm"),
     }

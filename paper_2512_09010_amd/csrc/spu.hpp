@@ -17,7 +17,7 @@ SpuLayout spu_layout(int B, int N, int D, int sigma);
 luvc_status spu_score_dense(const void* x, int B, int N, int D, int64_t row_stride, luvc_dtype dt, int sigma,
                             int use_hamming, float* scores, void* workspace, hipStream_t st);
 
-// Fast path (spu_fft.hip): N = 256 * N2, 2 * sigma + 1 <= 256.
+// Fast path (spu_fft.hip): N = 16 * Q * N2 with Q in {16, 15, 9}, 2 * sigma + 1 <= 16 * Q, N <= 4096.
 bool spu_fft_supported(int N, int sigma);
 luvc_status spu_score_fft(const void* x, int B, int N, int D, int64_t row_stride, luvc_dtype dt, int sigma,
                           const float2* tw, const float* gm, float* partial, int n_tiles, hipStream_t st);

@@ -1,19 +1,23 @@
-// SPU score (paper Section 3.3, Eq. 4-8): fast path for N = 256 * N2, 2*sigma + 1 <= 256.
+// SPU score (paper Section 3.3, Eq. 4-8): fast path for N = N1 * N2 with N1 = 16 * Q, Q in {16, 15, 9},
+// and 2*sigma + 1 <= N1 (N = 1024, 2048, 720, 144 ... of the benchmark workloads).
 //
 // Two real channels (d, d+1) are packed as one complex signal z = x_d + i x_{d+1}.  The mask of
 // Eq. 5 is real and symmetric in k, so the filter is a real linear operator and Re / Im of the
 // filtered z are the two filtered channels: no unpacking is ever needed.
 //
-// Transform decomposition along the token index, n = N2 * n1 + n2 (n1 < 256, n2 < N2):
-//   Eq. 4 on the pass band:  F[k] = sum_{n2} W_N^{k n2} Y_{n2}[k mod 256],  |k| <= sigma,
-//                            Y_{n2} = 256-point DFT of the stride-N2 subsequence n2;
+// Transform decomposition along the token index, n = N2 * n1 + n2 (n1 < N1, n2 < N2):
+//   Eq. 4 on the pass band:  F[k] = sum_{n2} W_N^{k n2} Y_{n2}[k mod N1],  |k| <= sigma,
+//                            Y_{n2} = N1-point DFT of the stride-N2 subsequence n2;
 //   Eq. 6:                   F[k] *= M[|k|] / N;
-//   Eq. 7:                   z'[N2 n1 + n2] = 256-point inverse DFT over k1 of F[k] W_N^{-k n2};
+//   Eq. 7:                   z'[N2 n1 + n2] = N1-point inverse DFT over k1 of F[k] W_N^{-k n2};
 //   Eq. 8:                   |z'|^2 summed over the channel pairs of the tile.
-// Each 256-point transform is 16 x 16: a radix-16 butterfly held in registers, one exchange through
-// LDS, a second radix-16.  A workgroup owns 16 channel pairs (32 channels, 64-byte row segments for
-// bf16); thread (c, t) = (pair, residue).  The pass-band accumulators F stay in registers across the
-// N2 subsequences, so x is read exactly once and nothing but N floats per tile is written.
+// Each N1-point transform is 16 x Q (n1 = Q j + t, k1 = ka + 16 kb): a radix-16 butterfly over j held
+// in registers, the twiddle W_N1^{t ka}, one exchange through LDS, and a Q-point transform over t
+// (radix-16 again, or 3 x 5 by the prime-factor map, or 3 x 3).  A workgroup owns 16 channel pairs
+// (32 channels, 64-byte row segments for bf16); thread (c, t) = (pair, residue): Q of the 16 residue
+// threads hold 16 points each for the radix-16 side, all 16 hold Q points each for the other side.
+// The pass-band accumulators F stay in registers across the N2 subsequences, so x is read exactly
+// once and nothing but N floats per tile is written.
 #include "common.hpp"
 #include "spu.hpp"
 
@@ -60,6 +64,84 @@ __device__ __forceinline__ void fft16(cf (&v)[16])
         for (int p = q + 1; p < 4; ++p) { const cf s = v[4 * q + p]; v[4 * q + p] = v[4 * p + q]; v[4 * p + q] = s; }
 }
 
+// 3-point DFT (INV: conjugate twiddles)
+template <bool INV>
+__device__ __forceinline__ void dft3(cf& a, cf& b, cf& c)
+{
+    constexpr float s3 = 0.8660254037844386f;
+    const cf t = b + c, m{a.x - 0.5f * t.x, a.y - 0.5f * t.y};
+    const cf d{(b.x - c.x) * s3, (b.y - c.y) * s3};
+    const cf r = INV ? cf{-d.y, d.x} : cf{d.y, -d.x};          // d * (+i) or d * (-i)
+    a = a + t; b = m + r; c = m - r;
+}
+
+// 5-point DFT
+template <bool INV>
+__device__ __forceinline__ void dft5(cf& x0, cf& x1, cf& x2, cf& x3, cf& x4)
+{
+    constexpr float c1 = 0.30901699437494745f, c2 = -0.8090169943749475f, s1 = 0.9510565162951535f, s2 = 0.5877852522924731f;
+    const cf t1 = x1 + x4, t2 = x2 + x3, t3 = x1 - x4, t4 = x2 - x3;
+    const cf m1{fmaf(c2, t2.x, fmaf(c1, t1.x, x0.x)), fmaf(c2, t2.y, fmaf(c1, t1.y, x0.y))};
+    const cf m2{fmaf(c1, t2.x, fmaf(c2, t1.x, x0.x)), fmaf(c1, t2.y, fmaf(c2, t1.y, x0.y))};
+    const cf u1{fmaf(s2, t4.x, s1 * t3.x), fmaf(s2, t4.y, s1 * t3.y)};
+    const cf u2{fmaf(-s1, t4.x, s2 * t3.x), fmaf(-s1, t4.y, s2 * t3.y)};
+    const cf r1 = INV ? cf{-u1.y, u1.x} : cf{u1.y, -u1.x};
+    const cf r2 = INV ? cf{-u2.y, u2.x} : cf{u2.y, -u2.x};
+    x0 = x0 + t1 + t2;
+    x1 = m1 + r1; x4 = m1 - r1;
+    x2 = m2 + r2; x3 = m2 - r2;
+}
+
+// Q-point DFT in registers, natural order in and out
+template <int Q, bool INV> struct dftq;
+template <bool INV> struct dftq<16, INV> {
+    __device__ static __forceinline__ void run(cf (&v)[16]) { fft16<INV>(v); }
+};
+template <bool INV> struct dftq<15, INV> {
+    // prime-factor map (no twiddles): n = (5 n1 + 3 n2) mod 15, k = (10 k1 + 6 k2) mod 15
+    __device__ static __forceinline__ void run(cf (&v)[15])
+    {
+        cf u[3][5];
+#pragma unroll
+        for (int n2 = 0; n2 < 5; ++n2) {
+            cf a = v[(3 * n2) % 15], b = v[(5 + 3 * n2) % 15], c = v[(10 + 3 * n2) % 15];
+            dft3<INV>(a, b, c);
+            u[0][n2] = a; u[1][n2] = b; u[2][n2] = c;
+        }
+#pragma unroll
+        for (int k1 = 0; k1 < 3; ++k1) {
+            dft5<INV>(u[k1][0], u[k1][1], u[k1][2], u[k1][3], u[k1][4]);
+#pragma unroll
+            for (int k2 = 0; k2 < 5; ++k2) v[(10 * k1 + 6 * k2) % 15] = u[k1][k2];
+        }
+    }
+};
+template <bool INV> struct dftq<9, INV> {
+    // 3 x 3: n = 3 n1 + n2, k = k1 + 3 k2, twiddle W_9^{n2 k1}
+    __device__ static __forceinline__ void run(cf (&v)[9])
+    {
+        constexpr float c1 = 0.766044443118978f, s1 = 0.6427876096865393f;      // W_9^1
+        constexpr float c2 = 0.17364817766693036f, s2 = 0.984807753012208f;     // W_9^2
+        constexpr float c4 = -0.9396926207859084f, s4 = 0.3420201433256687f;    // W_9^4
+        cf u[3][3];
+#pragma unroll
+        for (int n2 = 0; n2 < 3; ++n2) {
+            cf a = v[n2], b = v[3 + n2], c = v[6 + n2];
+            dft3<INV>(a, b, c);
+            u[0][n2] = a; u[1][n2] = b; u[2][n2] = c;
+        }
+        auto tw = [](cf a, cf w) { return INV ? cmulc(a, w) : cmul(a, w); };
+        u[1][1] = tw(u[1][1], cf{c1, -s1}); u[1][2] = tw(u[1][2], cf{c2, -s2});
+        u[2][1] = tw(u[2][1], cf{c2, -s2}); u[2][2] = tw(u[2][2], cf{c4, -s4});
+#pragma unroll
+        for (int k1 = 0; k1 < 3; ++k1) {
+            dft3<INV>(u[k1][0], u[k1][1], u[k1][2]);
+#pragma unroll
+            for (int k2 = 0; k2 < 3; ++k2) v[k1 + 3 * k2] = u[k1][k2];
+        }
+    }
+};
+
 typedef unsigned int u32x2 __attribute__((__vector_size__(8)));
 
 // One channel pair of one token.  Rows are addressed through a buffer resource that spans the whole
@@ -105,29 +187,31 @@ __device__ __forceinline__ float row16_sum(float v)
 
 }  // namespace
 
-template <typename T, bool POW2, bool ALIGNED>
+template <typename T, int Q, bool POW2, bool ALIGNED>
 __global__ void __launch_bounds__(256)
-spu_fft256(const T* __restrict__ x, int N, int D, int64_t row_stride, int sigma,
+spu_fft16q(const T* __restrict__ x, int N, int D, int64_t row_stride, int sigma,
            const float2* __restrict__ tw_g, const float* __restrict__ gm /* M[f]/N */,
            float* __restrict__ partial /* [B, n_tiles, N] */)
 {
     using pio = pair_io<T>;
+    constexpr int N1 = 16 * Q;
     extern __shared__ float2 smem[];
-    float2* xbuf = smem;                         // [16][kRowPad]  exchange between the two radix-16 passes
+    float2* xbuf = smem;                         // [16][kRowPad]  exchange between the two passes
     float2* tw = smem + 16 * kRowPad;            // [N]    (cos, sin)(2 pi i / N)
-    float2* tw256 = tw + N;                      // [256]  (cos, sin)(2 pi i / 256)
-    float* eperm = reinterpret_cast<float*>(tw256 + 256);   // [N2][16 t][16 j] energies of this tile
+    float2* tw1 = tw + N;                        // [N1]   (cos, sin)(2 pi i / N1)
+    float* eperm = reinterpret_cast<float*>(tw1 + N1);      // [N2][Q t][16 j] energies of this tile
     const int tid = threadIdx.x, c = tid & 15, t = tid >> 4;
     // neighbouring channel tiles share 128-byte lines of every token row: keep them on one XCD
     const int n_tiles = gridDim.x;
     const unsigned item = xcd_contiguous(blockIdx.x + gridDim.x * blockIdx.y, gridDim.x * gridDim.y);
     const int tile = item % n_tiles, b = item / n_tiles;
-    const int N2 = N >> 8;
+    const int N2 = N / N1;
     for (int i = tid; i < N; i += 256) tw[i] = tw_g[i];
-    tw256[tid] = tw_g[tid * N2];
+    if (tid < N1) tw1[tid] = tw_g[tid * N2];
 
     const int d0 = tile * 32 + 2 * c;
-    const bool live = d0 < D, second = d0 + 1 < D;
+    const bool rdx = Q == 16 || t < Q;           // this thread takes part in the radix-16 side
+    const bool live = d0 < D && rdx, second = d0 + 1 < D;
     const uint32_t es = (uint32_t)sizeof(T);
     const uint32_t row_bytes = (uint32_t)row_stride * es;
     // resource over sample b (N rows); lanes without a channel pair point past its end
@@ -136,13 +220,13 @@ spu_fft256(const T* __restrict__ x, int N, int D, int64_t row_stride, int sigma,
         const_cast<T*>(x) + (int64_t)b * N * row_stride, 0, (int)(span > 0x7fffffffull ? 0x7fffffffull : span), 0x00020000);
     const uint32_t lane_off = live ? (uint32_t)d0 * es : 0x80000000u;
 
-    // this thread's output bins of every 256-point transform: k1 = t + 16 kb (t doubles as ka)
-    int kpos[16], ph[16];
-    cf F[16];
+    // this thread's output bins of every N1-point transform: k1 = t + 16 kb (t doubles as ka)
+    int kpos[Q], ph[Q];
+    cf F[Q];
 #pragma unroll
-    for (int kb = 0; kb < 16; ++kb) {
+    for (int kb = 0; kb < Q; ++kb) {
         const int k1 = t + 16 * kb;
-        kpos[kb] = k1 <= sigma ? k1 : N - 256 + k1;       // k mod N (bins outside the band are masked later)
+        kpos[kb] = k1 <= sigma ? k1 : N - N1 + k1;        // k mod N (bins outside the band are masked later)
         ph[kb] = 0;                                        // (k * n2) mod N
         F[kb] = {0.f, 0.f};
     }
@@ -151,12 +235,18 @@ spu_fft256(const T* __restrict__ x, int N, int D, int64_t row_stride, int sigma,
         if (POW2) ph[kb] &= N - 1;
         else if (ph[kb] >= N) ph[kb] -= N;
     };
+    auto step1 = [&](int e) {                    // (e + t) mod N1
+        e += t;
+        if (Q == 16) e &= N1 - 1;
+        else if (e >= N1) e -= N1;
+        return e;
+    };
 
     typename pio::raw_t raw[16];
     auto load_sub = [&](int n2) {
 #pragma unroll
         for (int j = 0; j < 16; ++j)
-            raw[j] = pio::load(rsrc, lane_off + (uint32_t)(N2 * (16 * j + t) + n2) * row_bytes, second, ALIGNED);
+            raw[j] = pio::load(rsrc, lane_off + (uint32_t)(N2 * (Q * j + t) + n2) * row_bytes, second, ALIGNED);
     };
     load_sub(0);
     __syncthreads();                             // twiddle tables ready
@@ -167,98 +257,115 @@ spu_fft256(const T* __restrict__ x, int N, int D, int64_t row_stride, int sigma,
 #pragma unroll
         for (int j = 0; j < 16; ++j) v[j] = pio::widen(raw[j]);
         if (n2 + 1 < N2) load_sub(n2 + 1);       // next subsequence in flight while this one is transformed
-        fft16<false>(v);                         // over j -> ka
-        int e256 = 0;
+        if (rdx) {
+            fft16<false>(v);                     // over j -> ka
+            int e1 = 0;
 #pragma unroll
-        for (int ka = 0; ka < 16; ++ka) {
-            const float2 w = tw256[e256];
-            e256 = (e256 + t) & 255;
-            const cf r = cmulc(v[ka], cf{w.x, w.y});       // * W_256^{t ka}
-            xbuf[ka * kRowPad + t * kPairs + c] = make_float2(r.x, r.y);
+            for (int ka = 0; ka < 16; ++ka) {
+                const float2 w = tw1[e1];
+                e1 = step1(e1);
+                const cf r = cmulc(v[ka], cf{w.x, w.y});   // * W_N1^{t ka}
+                xbuf[ka * kRowPad + t * kPairs + c] = make_float2(r.x, r.y);
+            }
         }
         __syncthreads();
+        cf u[Q];
 #pragma unroll
-        for (int s = 0; s < 16; ++s) { const float2 q = xbuf[t * kRowPad + s * kPairs + c]; v[s] = {q.x, q.y}; }
+        for (int s = 0; s < Q; ++s) { const float2 q = xbuf[t * kRowPad + s * kPairs + c]; u[s] = {q.x, q.y}; }
         __syncthreads();
-        fft16<false>(v);                         // over the residue -> kb ; v[kb] = Y[t + 16 kb]
+        dftq<Q, false>::run(u);                  // over the residue -> kb ; u[kb] = Y[t + 16 kb]
 #pragma unroll
-        for (int kb = 0; kb < 16; ++kb) {
+        for (int kb = 0; kb < Q; ++kb) {
             const float2 w = tw[ph[kb]];
-            F[kb] = F[kb] + cmulc(v[kb], cf{w.x, w.y});    // * W_N^{k n2}
+            F[kb] = F[kb] + cmulc(u[kb], cf{w.x, w.y});    // * W_N^{k n2}
             advance(kb);
         }
     }
     // ------------------------------------------------------------------ mask (Eq. 5-6) with the 1/N of Eq. 7
 #pragma unroll
-    for (int kb = 0; kb < 16; ++kb) {
+    for (int kb = 0; kb < Q; ++kb) {
         const int k1 = t + 16 * kb;
-        const bool lo = k1 <= sigma, hi = k1 >= 256 - sigma;
-        const float g = (lo || hi) ? gm[lo ? k1 : 256 - k1] : 0.f;
+        const bool lo = k1 <= sigma, hi = k1 >= N1 - sigma;
+        const float g = (lo || hi) ? gm[lo ? k1 : N1 - k1] : 0.f;
         F[kb] = {F[kb].x * g, F[kb].y * g};
         ph[kb] = 0;
     }
     // ------------------------------------------------------------------ inverse (Eq. 7) and energy (Eq. 8)
     for (int n2 = 0; n2 < N2; ++n2) {
-        cf v[16];
+        cf u[Q];
 #pragma unroll
-        for (int kb = 0; kb < 16; ++kb) {
+        for (int kb = 0; kb < Q; ++kb) {
             const float2 w = tw[ph[kb]];
-            v[kb] = cmul(F[kb], cf{w.x, w.y});   // F[k] W_N^{-k n2}
+            u[kb] = cmul(F[kb], cf{w.x, w.y});   // F[k] W_N^{-k n2}
             advance(kb);
         }
-        fft16<true>(v);                          // over kb -> residue s
-        int e256 = 0;
+        dftq<Q, true>::run(u);                   // over kb -> residue s
+        int e1 = 0;
 #pragma unroll
-        for (int s = 0; s < 16; ++s) {
-            const float2 w = tw256[e256];
-            e256 = (e256 + t) & 255;
-            const cf r = cmul(v[s], cf{w.x, w.y});
+        for (int s = 0; s < Q; ++s) {
+            const float2 w = tw1[e1];
+            e1 = step1(e1);
+            const cf r = cmul(u[s], cf{w.x, w.y});         // * W_N1^{-s ka}
             xbuf[s * kRowPad + t * kPairs + c] = make_float2(r.x, r.y);
         }
         __syncthreads();
+        if (rdx) {
+            cf v[16];
 #pragma unroll
-        for (int ka = 0; ka < 16; ++ka) { const float2 q = xbuf[t * kRowPad + ka * kPairs + c]; v[ka] = {q.x, q.y}; }
-        __syncthreads();
-        fft16<true>(v);                          // over ka -> j ; v[j] = z'[N2 (16 j + t) + n2]
-        float e[16];
+            for (int ka = 0; ka < 16; ++ka) { const float2 q = xbuf[t * kRowPad + ka * kPairs + c]; v[ka] = {q.x, q.y}; }
+            fft16<true>(v);                      // over ka -> j ; v[j] = z'[N2 (Q j + t) + n2]
+            float e[16];
 #pragma unroll
-        for (int j = 0; j < 16; ++j) e[j] = row16_sum(fmaf(v[j].x, v[j].x, v[j].y * v[j].y));   // over the 16 pairs
-        if (c == 0) {
-            float4* dst = reinterpret_cast<float4*>(eperm + (n2 * 16 + t) * 16);
+            for (int j = 0; j < 16; ++j) e[j] = row16_sum(fmaf(v[j].x, v[j].x, v[j].y * v[j].y));   // over the 16 pairs
+            if (c == 0) {
+                float4* dst = reinterpret_cast<float4*>(eperm + (n2 * Q + t) * 16);
 #pragma unroll
-            for (int q = 0; q < 4; ++q) dst[q] = make_float4(e[4 * q], e[4 * q + 1], e[4 * q + 2], e[4 * q + 3]);
+                for (int q = 0; q < 4; ++q) dst[q] = make_float4(e[4 * q], e[4 * q + 1], e[4 * q + 2], e[4 * q + 3]);
+            }
         }
+        __syncthreads();
     }
-    __syncthreads();
     float* pout = partial + ((int64_t)b * n_tiles + tile) * N;
-    for (int n = tid; n < N; n += 256) {         // n = N2 (16 j + t') + n2
+    for (int n = tid; n < N; n += 256) {         // n = N2 (Q j + t') + n2
         const int n2 = POW2 ? (n & (N2 - 1)) : n % N2;
         const int q = (n - n2) / N2;
-        pout[n] = eperm[(n2 * 16 + (q & 15)) * 16 + (q >> 4)];
+        const int tq = Q == 16 ? (q & 15) : q % Q, j = Q == 16 ? (q >> 4) : q / Q;
+        pout[n] = eperm[(n2 * Q + tq) * 16 + j];
     }
 }
 
-static size_t fft_lds_bytes(int N) { return sizeof(float2) * (size_t)(16 * kRowPad + N + 256) + sizeof(float) * (size_t)N; }
+static size_t fft_lds_bytes(int N, int Q) { return sizeof(float2) * (size_t)(16 * kRowPad + N + 16 * Q) + sizeof(float) * (size_t)N; }
 
-bool spu_fft_supported(int N, int sigma)
+// the residue-side length Q of the 16 x Q transform that serves (N, sigma); 0 if none does
+static int fft_pick_q(int N, int sigma)
 {
-    return N >= 256 && N % 256 == 0 && N <= 4096 && 2 * sigma + 1 <= 256;
+    if (N > 4096) return 0;
+    for (int Q : {16, 15, 9}) {
+        const int N1 = 16 * Q;
+        if (N % N1 == 0 && 2 * sigma + 1 <= N1) return Q;
+    }
+    return 0;
 }
+
+bool spu_fft_supported(int N, int sigma) { return fft_pick_q(N, sigma) != 0; }
 
 luvc_status spu_score_fft(const void* x, int B, int N, int D, int64_t row_stride, luvc_dtype dt, int sigma,
                           const float2* tw, const float* gm, float* partial, int n_tiles, hipStream_t st)
 {
     const dim3 grid((unsigned)n_tiles, (unsigned)B);
-    const size_t lds = fft_lds_bytes(N);
+    const int Q = fft_pick_q(N, sigma);
+    const size_t lds = fft_lds_bytes(N, Q);
     const bool pow2 = (N & (N - 1)) == 0;
     // channel pairs are fetched with one access when every pair is naturally aligned
     const size_t pair_bytes = dt == LUVC_F32 ? 8 : 4;
     const bool aligned = (row_stride % 2 == 0) && ((uintptr_t)x % pair_bytes == 0) && (D % 2 == 0);
-#define LUVC_FFT(TT, P2, AL) LUVC_LAUNCH("spu_fft256", (spu_fft256<TT, P2, AL>), grid, dim3(256), lds, st, (const TT*)x, N, D, row_stride, sigma, tw, gm, partial)
-#define LUVC_FFT_T(TT) do { if (pow2) { if (aligned) LUVC_FFT(TT, true, true); else LUVC_FFT(TT, true, false); } \
-                            else { if (aligned) LUVC_FFT(TT, false, true); else LUVC_FFT(TT, false, false); } } while (0)
+#define LUVC_FFT(TT, QQ, P2, AL) LUVC_LAUNCH("spu_fft", (spu_fft16q<TT, QQ, P2, AL>), grid, dim3(256), lds, st, (const TT*)x, N, D, row_stride, sigma, tw, gm, partial)
+#define LUVC_FFT_A(TT, QQ, P2) do { if (aligned) LUVC_FFT(TT, QQ, P2, true); else LUVC_FFT(TT, QQ, P2, false); } while (0)
+#define LUVC_FFT_T(TT) do { if (Q == 16) { if (pow2) LUVC_FFT_A(TT, 16, true); else LUVC_FFT_A(TT, 16, false); } \
+                            else if (Q == 15) LUVC_FFT_A(TT, 15, false); else LUVC_FFT_A(TT, 9, false); } while (0)
     if (dt == LUVC_F32) LUVC_FFT_T(float); else LUVC_FFT_T(bf16_t);
 #undef LUVC_FFT_T
+#undef LUVC_FFT_A
 #undef LUVC_FFT
     return check_launch("spu score (fft)");
 }

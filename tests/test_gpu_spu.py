@@ -35,9 +35,11 @@ def score_case(oracle, x_io, dtype, sigma, ham=True, tag="", stride_pad=0):
 @pytest.mark.parametrize("B,N,D,sigma", [
     (1, 1, 8, 0), (1, 2, 8, 1), (2, 5, 3, 2), (2, 16, 64, 3), (1, 97, 70, 10), (2, 144, 200, 18),
     (1, 196, 130, 4), (1, 256, 64, 128), (2, 130, 65, 0), (1, 300, 96, 31),
-    # shapes served by the transform-decomposition FFT path (N = 256 * N2, 2 sigma + 1 <= 256)
+    # shapes served by the transform-decomposition FFT path (N = 16 Q N2 with Q = 16, 15 or 9, 2 sigma + 1 <= 16 Q)
     (2, 256, 64, 20), (1, 256, 32, 127), (1, 512, 70, 127), (1, 768, 33, 50), (2, 1024, 96, 102), (1, 2048, 40, 0),
     (1, 1280, 31, 64),
+    (2, 240, 64, 119), (1, 240, 33, 0), (2, 720, 70, 54), (1, 480, 40, 60), (1, 1200, 34, 100),      # Q = 15
+    (2, 144, 64, 71), (1, 144, 200, 18), (1, 288, 37, 30), (1, 432, 64, 72), (1, 1008, 32, 7),       # Q = 9
 ])
 def test_score_small_random(oracle, dtype, B, N, D, sigma):
     rng = np.random.default_rng(N * 31 + D)
