@@ -155,7 +155,7 @@ def main():
         "oim_halve_pair": (oim_bytes, None, "hbm"), "oim_halve": (oim_bytes, None, "hbm"),
         "spu_fft": (score_bytes, fft_flops, "alu"),
         "spu_fwd_dense": (score_bytes, None, "hbm"),
-        "spu_gather": (prune_bytes, None, "hbm"),
+        "spu_gather": (prune_bytes, None, "hbm"), "spu_prune_fused": (prune_bytes, None, "hbm"),
     }
     try:
         with open(os.path.join(ROOT, "profiles", "hbm_traffic.json")) as f:

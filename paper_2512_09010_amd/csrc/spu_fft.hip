@@ -18,6 +18,8 @@
 // threads hold 16 points each for the radix-16 side, all 16 hold Q points each for the other side.
 // The pass-band accumulators F stay in registers across the N2 subsequences, so x is read exactly
 // once and nothing but N floats per tile is written.
+#include <atomic>
+
 #include "common.hpp"
 #include "spu.hpp"
 
@@ -173,6 +175,7 @@ template <> struct pair_io<float> {
 };
 
 constexpr int kPairs = 16;                       // channel pairs per workgroup
+constexpr int kTileGroup = 8;                    // channel tiles whose energies are added in one go
 constexpr int kRowPad = 16 * kPairs + kPairs;    // float2 per exchange row: 16 x 16 pairs + one pad group
 
 // sum over the 16 lanes of a DPP row; every lane of the row ends up with the total, fixed order
@@ -189,9 +192,9 @@ __device__ __forceinline__ float row16_sum(float v)
 
 template <typename T, int Q, bool POW2, bool ALIGNED>
 __global__ void __launch_bounds__(256)
-spu_fft16q(const T* __restrict__ x, int N, int D, int64_t row_stride, int sigma,
-           const float2* __restrict__ tw_g, const float* __restrict__ gm /* M[f]/N */,
-           float* __restrict__ partial /* [B, n_tiles, N] */)
+spu_fft16q(const T* __restrict__ x, int N, int D, int64_t row_stride, int sigma, int use_hamming,
+           float* __restrict__ partial /* [B, n_tiles, N] */, float* __restrict__ gpartial /* [B, n_groups, N] */,
+           unsigned int* __restrict__ done /* [B][1 + n_groups], zero between calls */, float* __restrict__ scores /* [B, N] */)
 {
     using pio = pair_io<T>;
     constexpr int N1 = 16 * Q;
@@ -200,14 +203,14 @@ spu_fft16q(const T* __restrict__ x, int N, int D, int64_t row_stride, int sigma,
     float2* tw = smem + 16 * kRowPad;            // [N]    (cos, sin)(2 pi i / N)
     float2* tw1 = tw + N;                        // [N1]   (cos, sin)(2 pi i / N1)
     float* eperm = reinterpret_cast<float*>(tw1 + N1);      // [N2][Q t][16 j] energies of this tile
+    float* gm = eperm + N;                       // [sigma + 1]  M[f] / N  (Eq. 5 with the 1/N of Eq. 7)
+    __shared__ bool is_last;
     const int tid = threadIdx.x, c = tid & 15, t = tid >> 4;
     // neighbouring channel tiles share 128-byte lines of every token row: keep them on one XCD
     const int n_tiles = gridDim.x;
     const unsigned item = xcd_contiguous(blockIdx.x + gridDim.x * blockIdx.y, gridDim.x * gridDim.y);
     const int tile = item % n_tiles, b = item / n_tiles;
     const int N2 = N / N1;
-    for (int i = tid; i < N; i += 256) tw[i] = tw_g[i];
-    if (tid < N1) tw1[tid] = tw_g[tid * N2];
 
     const int d0 = tile * 32 + 2 * c;
     const bool rdx = Q == 16 || t < Q;           // this thread takes part in the radix-16 side
@@ -249,6 +252,31 @@ spu_fft16q(const T* __restrict__ x, int N, int D, int64_t row_stride, int sigma,
             raw[j] = pio::load(rsrc, lane_off + (uint32_t)(N2 * (Q * j + t) + n2) * row_bytes, second, ALIGNED);
     };
     load_sub(0);
+    // Tables, built while the first loads are in flight.  One octant of the circle is evaluated in fp64
+    // and rounded once; the other seven follow by symmetry (8 divides N).
+    {
+        const int n8 = N >> 3, n4 = N >> 2, nh = N >> 1, n34 = nh + n4;
+        for (int i = tid; i <= n8; i += 256) {
+            double sd, cd;
+            sincospi(2.0 * (double)i / (double)N, &sd, &cd);
+            const float cs = (float)cd, sn = (float)sd;
+            tw[i] = make_float2(cs, sn);
+            tw[n4 - i] = make_float2(sn, cs);
+            tw[n4 + i] = make_float2(-sn, cs);
+            tw[nh - i] = make_float2(-cs, sn);
+            tw[nh + i] = make_float2(-cs, -sn);
+            tw[n34 - i] = make_float2(-sn, -cs);
+            tw[n34 + i] = make_float2(sn, -cs);
+            if (i) tw[N - i] = make_float2(cs, -sn);
+        }
+        if (tid <= sigma) {
+            double w = 1.0;
+            if (use_hamming) w = 0.54 + 0.46 * cospi(2.0 * (double)tid / (double)(N - 1));
+            gm[tid] = (float)(w / (double)N);
+        }
+    }
+    __syncthreads();
+    if (tid < N1) tw1[tid] = tw[tid * N2];
     __syncthreads();                             // twiddle tables ready
 
     // ------------------------------------------------------------------ forward (Eq. 4 on the pass band)
@@ -325,16 +353,74 @@ spu_fft16q(const T* __restrict__ x, int N, int D, int64_t row_stride, int sigma,
         }
         __syncthreads();
     }
-    float* pout = partial + ((int64_t)b * n_tiles + tile) * N;
+    // The tile's energies go out as device-scope (write-through) stores and are read back below with
+    // device-scope loads: the other workgroups of the sample run on other XCDs, whose L2s are not kept
+    // coherent with this one, and a full release / acquire fence (an L2 write-back and invalidate per
+    // workgroup) costs more than the whole transform.
+    unsigned int* pout = reinterpret_cast<unsigned int*>(partial + ((int64_t)b * n_tiles + tile) * N);
     for (int n = tid; n < N; n += 256) {         // n = N2 (Q j + t') + n2
         const int n2 = POW2 ? (n & (N2 - 1)) : n % N2;
         const int q = (n - n2) / N2;
         const int tq = Q == 16 ? (q & 15) : q % Q, j = Q == 16 ? (q >> 4) : q / Q;
-        pout[n] = eperm[(n2 * Q + tq) * 16 + j];
+        __hip_atomic_store(pout + n, __float_as_uint(eperm[(n2 * Q + tq) * 16 + j]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    // ------------------------------------------------------------------ Eq. 8 across the channel tiles
+    // Two levels, both in index order so that the result does not depend on which workgroup does the
+    // adding: the workgroup that completes a group of kTileGroup tiles last adds those tiles; the one
+    // that completes the last group of the sample adds the groups and takes the square root.  Every
+    // counter wraps back to zero.
+    const int n_groups = (n_tiles + kTileGroup - 1) / kTileGroup;
+    const int grp = tile / kTileGroup, t_first = grp * kTileGroup;
+    const int t_cnt = n_tiles - t_first < kTileGroup ? n_tiles - t_first : kTileGroup;
+    unsigned int* cnt = done + (int64_t)b * (n_groups + 1);
+    const int nh = N >> 1;                       // 2 divides N
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");       // this wavefront's stores have been performed
+    __syncthreads();
+    if (tid == 0) is_last = atomicInc(cnt + 1 + grp, (unsigned)t_cnt - 1u) == (unsigned)t_cnt - 1u;
+    __syncthreads();
+    if (!is_last) return;
+    {
+        const unsigned long long* pin = reinterpret_cast<const unsigned long long*>(partial + ((int64_t)b * n_tiles + t_first) * N);
+        unsigned long long* gout = reinterpret_cast<unsigned long long*>(gpartial + ((int64_t)b * n_groups + grp) * N);
+        for (int i = tid; i < nh; i += 256) {
+            unsigned long long p[kTileGroup];
+#pragma unroll
+            for (int tl = 0; tl < kTileGroup; ++tl)
+                p[tl] = tl < t_cnt ? __hip_atomic_load(pin + (int64_t)tl * nh + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0ull;
+            double e0 = 0.0, e1 = 0.0;
+#pragma unroll
+            for (int tl = 0; tl < kTileGroup; ++tl) {
+                e0 += (double)__uint_as_float((unsigned int)p[tl]);
+                e1 += (double)__uint_as_float((unsigned int)(p[tl] >> 32));
+            }
+            const unsigned long long r = (unsigned long long)__float_as_uint((float)e0) | ((unsigned long long)__float_as_uint((float)e1) << 32);
+            __hip_atomic_store(gout + i, r, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();                             // also: every thread has read is_last
+    if (tid == 0) is_last = atomicInc(cnt, (unsigned)n_groups - 1u) == (unsigned)n_groups - 1u;
+    __syncthreads();
+    if (!is_last) return;
+    const unsigned long long* gin = reinterpret_cast<const unsigned long long*>(gpartial + (int64_t)b * n_groups * N);
+    for (int i = tid; i < nh; i += 256) {
+        double e0 = 0.0, e1 = 0.0;
+#pragma unroll 8
+        for (int gi = 0; gi < n_groups; ++gi) {
+            const unsigned long long p = __hip_atomic_load(gin + (int64_t)gi * nh + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            e0 += (double)__uint_as_float((unsigned int)p);
+            e1 += (double)__uint_as_float((unsigned int)(p >> 32));
+        }
+        float* so = scores + (int64_t)b * N + 2 * i;
+        so[0] = (float)sqrt(e0);
+        so[1] = (float)sqrt(e1);
     }
 }
 
-static size_t fft_lds_bytes(int N, int Q) { return sizeof(float2) * (size_t)(16 * kRowPad + N + 16 * Q) + sizeof(float) * (size_t)N; }
+static size_t fft_lds_bytes(int N, int Q, int sigma)
+{
+    return sizeof(float2) * (size_t)(16 * kRowPad + N + 16 * Q) + sizeof(float) * (size_t)(N + sigma + 1);
+}
 
 // the residue-side length Q of the 16 x Q transform that serves (N, sigma); 0 if none does
 static int fft_pick_q(int N, int sigma)
@@ -349,21 +435,43 @@ static int fft_pick_q(int N, int sigma)
 
 bool spu_fft_supported(int N, int sigma) { return fft_pick_q(N, sigma) != 0; }
 
-luvc_status spu_score_fft(const void* x, int B, int N, int D, int64_t row_stride, luvc_dtype dt, int sigma,
-                          const float2* tw, const float* gm, float* partial, int n_tiles, hipStream_t st)
+// Completion counters of the samples in flight (one per sample and one per tile group of a sample), one
+// set per call slot.  They are zero whenever no call that uses the slot is running: the workgroup that
+// finds a counter complete wraps it back to zero.
+constexpr int kSlotCounters = 16384, kSlots = 64;
+__device__ unsigned int g_fft_done[kSlots * kSlotCounters];
+static std::atomic<unsigned> g_fft_slot{0};
+
+int spu_fft_groups(int n_tiles) { return (n_tiles + kTileGroup - 1) / kTileGroup; }
+
+luvc_status spu_score_fft(const void* x, int B, int N, int D, int64_t row_stride, luvc_dtype dt, int sigma, int use_hamming,
+                          float* partial, float* gpartial, int n_tiles, float* scores, hipStream_t st)
 {
-    const dim3 grid((unsigned)n_tiles, (unsigned)B);
     const int Q = fft_pick_q(N, sigma);
-    const size_t lds = fft_lds_bytes(N, Q);
+    const size_t lds = fft_lds_bytes(N, Q, sigma);
     const bool pow2 = (N & (N - 1)) == 0;
     // channel pairs are fetched with one access when every pair is naturally aligned
-    const size_t pair_bytes = dt == LUVC_F32 ? 8 : 4;
-    const bool aligned = (row_stride % 2 == 0) && ((uintptr_t)x % pair_bytes == 0) && (D % 2 == 0);
-#define LUVC_FFT(TT, QQ, P2, AL) LUVC_LAUNCH("spu_fft", (spu_fft16q<TT, QQ, P2, AL>), grid, dim3(256), lds, st, (const TT*)x, N, D, row_stride, sigma, tw, gm, partial)
+    const size_t es = dt == LUVC_F32 ? 4 : 2;
+    const bool aligned = (row_stride % 2 == 0) && ((uintptr_t)x % (2 * es) == 0) && (D % 2 == 0);
+    const int n_groups = spu_fft_groups(n_tiles);
+    if (n_groups + 1 > kSlotCounters) { set_error("D=%d exceeds the supported width of the fft path", D); return LUVC_ERR_UNSUPPORTED; }
+    const int per_launch = kSlotCounters / (n_groups + 1);       // samples whose counters fit one slot
+    unsigned int* done_base = nullptr;
+    if (hipGetSymbolAddress((void**)&done_base, HIP_SYMBOL(g_fft_done)) != hipSuccess) return check_launch("spu score (counters)");
+#define LUVC_FFT(TT, QQ, P2, AL) LUVC_LAUNCH("spu_fft", (spu_fft16q<TT, QQ, P2, AL>), grid, dim3(256), lds, st, (const TT*)xs, N, D, row_stride, sigma, use_hamming, ps, gs, done, ss)
 #define LUVC_FFT_A(TT, QQ, P2) do { if (aligned) LUVC_FFT(TT, QQ, P2, true); else LUVC_FFT(TT, QQ, P2, false); } while (0)
 #define LUVC_FFT_T(TT) do { if (Q == 16) { if (pow2) LUVC_FFT_A(TT, 16, true); else LUVC_FFT_A(TT, 16, false); } \
                             else if (Q == 15) LUVC_FFT_A(TT, 15, false); else LUVC_FFT_A(TT, 9, false); } while (0)
-    if (dt == LUVC_F32) LUVC_FFT_T(float); else LUVC_FFT_T(bf16_t);
+    for (int b0 = 0; b0 < B; b0 += per_launch) {
+        const int nb = B - b0 < per_launch ? B - b0 : per_launch;
+        const dim3 grid((unsigned)n_tiles, (unsigned)nb);
+        const char* xs = (const char*)x + (size_t)b0 * N * row_stride * es;
+        float* ps = partial + (size_t)b0 * n_tiles * N;
+        float* gs = gpartial + (size_t)b0 * n_groups * N;
+        float* ss = scores + (size_t)b0 * N;
+        unsigned int* done = done_base + (size_t)(g_fft_slot.fetch_add(1) % kSlots) * kSlotCounters;
+        if (dt == LUVC_F32) LUVC_FFT_T(float); else LUVC_FFT_T(bf16_t);
+    }
 #undef LUVC_FFT_T
 #undef LUVC_FFT_A
 #undef LUVC_FFT

@@ -148,15 +148,146 @@ spu_gather(const unsigned char* __restrict__ x, const int32_t* __restrict__ kept
     }
 }
 
+// ------------------------------------------------------------------ select + gather in one launch (N <= 4096)
+// Workgroup (g, b) of 256 threads repeats the selection of sample b on its own (the scores of a sample
+// are a few KB, and the groups run side by side), keeps the list of kept tokens in LDS, and then copies
+// its share of the kept rows: row q goes to wavefront q mod (4 G) of the sample.  Group 0 also writes
+// kept_idx.  Compared with a selection launch followed by a gather launch this saves a dispatch and the
+// wait between the two, which is most of the time at these sizes.
+constexpr int kFusedMaxN = 4096, kFusedThreads = 256, kFusedKeys = kFusedMaxN / kFusedThreads;
+
+template <int BYTES>
+__global__ void __launch_bounds__(kFusedThreads)
+spu_prune_fused(const unsigned char* __restrict__ x, const float* __restrict__ scores, int N, int n_keep,
+                int64_t row_bytes_in, int64_t row_bytes_out, int32_t* __restrict__ kept_idx, unsigned char* __restrict__ x_out)
+{
+    __shared__ uint32_t keys[kFusedMaxN];
+    __shared__ int32_t kept[kFusedMaxN];
+    __shared__ int hist[256];
+    __shared__ uint32_t wave_tot[4];
+    __shared__ uint32_t sh_prefix;
+    __shared__ int sh_remaining;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int g = blockIdx.x, G = gridDim.x, b = blockIdx.y;
+    const float* s = scores + (int64_t)b * N;
+    for (int n = tid; n < N; n += kFusedThreads) keys[n] = score_key(s[n]);
+    hist[tid] = 0;
+    __syncthreads();
+    // thread tid owns the K consecutive tokens tid * K .. tid * K + K - 1
+    const int K = (N + kFusedThreads - 1) / kFusedThreads, n0 = tid * K;
+    uint32_t key[kFusedKeys];
+#pragma unroll
+    for (int i = 0; i < kFusedKeys; ++i) key[i] = (i < K && n0 + i < N) ? keys[n0 + i] : 0u;
+
+    uint32_t prefix = 0, mask = 0;
+    int remaining = n_keep;                            // still to pick among keys matching the prefix
+    for (int shift = 24; shift >= 0; shift -= 8) {
+#pragma unroll
+        for (int i = 0; i < kFusedKeys; ++i)
+            if (i < K && n0 + i < N && (key[i] & mask) == prefix) atomicAdd(&hist[(key[i] >> shift) & 255u], 1);
+        __syncthreads();
+        if (wave == 0) {
+            // lane l looks at digits 255 - 4 l .. 252 - 4 l, largest first
+            int h[4], sum = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) { h[j] = hist[255 - 4 * lane - j]; sum += h[j]; }
+            int incl = sum;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const int t = __shfl_up(incl, o, kWave);
+                if (lane >= o) incl += t;
+            }
+            int above = incl - sum;                    // tokens with a larger digit
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (above < remaining && remaining <= above + h[j]) {
+                    sh_prefix = prefix | ((uint32_t)(255 - 4 * lane - j) << shift);
+                    sh_remaining = remaining - above;
+                }
+                above += h[j];
+            }
+        }
+        __syncthreads();
+        prefix = sh_prefix;
+        remaining = sh_remaining;
+        mask |= 255u << shift;
+        hist[tid] = 0;                                 // every wave has passed the barrier after the read above
+        __syncthreads();
+    }
+    const uint32_t T = prefix;                         // key of the n_keep-th largest score
+    const int take_eq = remaining;                     // tokens with key == T that are kept (lowest indices)
+
+    // one scan for both counts: tokens above T in the low half, tokens equal to T in the high half
+    uint32_t cnt = 0;
+#pragma unroll
+    for (int i = 0; i < kFusedKeys; ++i)
+        if (i < K && n0 + i < N) cnt += (key[i] > T ? 1u : 0u) + (key[i] == T ? 0x10000u : 0u);
+    uint32_t incl = cnt;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t t = __shfl_up(incl, o, kWave);
+        if (lane >= o) incl += t;
+    }
+    if (lane == 63) wave_tot[wave] = incl;
+    __syncthreads();
+    uint32_t before = incl - cnt;
+    for (int w = 0; w < wave; ++w) before += wave_tot[w];
+    int eq_rank = (int)(before >> 16);
+    int pos = (int)(before & 0xffffu) + (eq_rank < take_eq ? eq_rank : take_eq);
+#pragma unroll
+    for (int i = 0; i < kFusedKeys; ++i) {
+        if (i < K && n0 + i < N) {
+            const bool eq = key[i] == T;
+            if (key[i] > T || (eq && eq_rank < take_eq)) {
+                if (pos < n_keep) kept[pos] = n0 + i;
+                ++pos;
+            }
+            eq_rank += eq ? 1 : 0;
+        }
+    }
+    __syncthreads();
+    if (g == 0)
+        for (int q = tid; q < n_keep; q += kFusedThreads) kept_idx[(int64_t)b * n_keep + q] = kept[q];
+    if (!x_out) return;
+    for (int q = g * 4 + wave; q < n_keep; q += G * 4) {
+        int src = kept[q];
+        src = src < 0 ? 0 : (src >= N ? N - 1 : src);  // in bounds whatever the scores held
+        const unsigned char* in = x + ((int64_t)b * N + src) * row_bytes_in;
+        unsigned char* o = x_out + ((int64_t)b * n_keep + q) * row_bytes_out;
+        if (BYTES == 16) {
+            for (int64_t i = (int64_t)lane * 16; i < row_bytes_out; i += 64 * 16)
+                *reinterpret_cast<uint4*>(o + i) = *reinterpret_cast<const uint4*>(in + i);
+        } else if (BYTES == 4) {
+            for (int64_t i = (int64_t)lane * 4; i < row_bytes_out; i += 64 * 4)
+                *reinterpret_cast<uint32_t*>(o + i) = *reinterpret_cast<const uint32_t*>(in + i);
+        } else {
+            for (int64_t i = (int64_t)lane * 2; i < row_bytes_out; i += 64 * 2)
+                *reinterpret_cast<uint16_t*>(o + i) = *reinterpret_cast<const uint16_t*>(in + i);
+        }
+    }
+}
+
 luvc_status spu_prune_run(const void* x, const float* scores, int B, int N, int D, int64_t row_stride, luvc_dtype dt,
                           int n_keep, int32_t* kept_idx, void* x_out, hipStream_t st)
 {
+    const int es = dt == LUVC_F32 ? 4 : 2;
+    const int64_t rin = row_stride * es, rout = (int64_t)D * es, rows = (int64_t)B * n_keep;
+    const bool v16 = x_out && rin % 16 == 0 && rout % 16 == 0 && ((uintptr_t)x % 16 == 0) && ((uintptr_t)x_out % 16 == 0);
+    if (N <= kFusedMaxN && B <= 65535) {
+        int G = x_out ? (n_keep + 3) / 4 : 1;          // one kept row per wavefront, up to 256 groups per sample
+        G = G > 256 ? 256 : G;
+        const dim3 grid((unsigned)G, (unsigned)B);
+        if (v16 || !x_out)
+            LUVC_LAUNCH("spu_prune_fused", (spu_prune_fused<16>), grid, dim3(kFusedThreads), 0, st, (const unsigned char*)x, scores, N, n_keep, rin, rout, kept_idx, (unsigned char*)x_out);
+        else if (es == 4)
+            LUVC_LAUNCH("spu_prune_fused", (spu_prune_fused<4>), grid, dim3(kFusedThreads), 0, st, (const unsigned char*)x, scores, N, n_keep, rin, rout, kept_idx, (unsigned char*)x_out);
+        else
+            LUVC_LAUNCH("spu_prune_fused", (spu_prune_fused<2>), grid, dim3(kFusedThreads), 0, st, (const unsigned char*)x, scores, N, n_keep, rin, rout, kept_idx, (unsigned char*)x_out);
+        return check_launch("spu prune");
+    }
     LUVC_LAUNCH("spu_select", spu_select, dim3((unsigned)B), dim3(kSelThreads), 0, st, scores, N, n_keep, kept_idx);
     if (x_out) {
-        const int es = dt == LUVC_F32 ? 4 : 2;
-        const int64_t rin = row_stride * es, rout = (int64_t)D * es, rows = (int64_t)B * n_keep;
         const unsigned g = (unsigned)((rows * 64 + 255) / 256);
-        const bool v16 = rin % 16 == 0 && rout % 16 == 0 && ((uintptr_t)x % 16 == 0) && ((uintptr_t)x_out % 16 == 0);
         if (v16)
             LUVC_LAUNCH("spu_gather", (spu_gather<16>), dim3(g), dim3(256), 0, st, (const unsigned char*)x, kept_idx, N, n_keep, rin, rout, rows, (unsigned char*)x_out);
         else if (es == 4)

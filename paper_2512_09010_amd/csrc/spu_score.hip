@@ -153,12 +153,14 @@ SpuLayout spu_layout(int B, int N, int D, int sigma)
     L.n_tiles = L.fast ? (D + 31) / 32 : (D + 63) / 64;
     const size_t spec = L.fast ? 0 : (size_t)B * (sigma + 1) * D;   // pass-band spectra of the direct path
     size_t off = 0;
-    L.tw = off;      off += align_up(sizeof(float2) * (size_t)N);
-    L.gk = off;      off += align_up(sizeof(float) * (size_t)(sigma + 1));
-    L.gm = off;      off += align_up(sizeof(float) * (size_t)(sigma + 1));
+    // the fast path builds its tables in LDS
+    L.tw = off;      off += L.fast ? 0 : align_up(sizeof(float2) * (size_t)N);
+    L.gk = off;      off += L.fast ? 0 : align_up(sizeof(float) * (size_t)(sigma + 1));
+    L.gm = off;      off += L.fast ? 0 : align_up(sizeof(float) * (size_t)(sigma + 1));
     L.Fc = off;      off += align_up(sizeof(float) * spec);
     L.Fs = off;      off += align_up(sizeof(float) * spec);
     L.partial = off; off += align_up(sizeof(float) * (size_t)B * L.n_tiles * N);
+    L.gpartial = off; off += L.fast ? align_up(sizeof(float) * (size_t)B * spu_fft_groups(L.n_tiles) * N) : 0;
     L.bytes = off;
     return L;
 }
@@ -174,14 +176,9 @@ luvc_status spu_score_dense(const void* x, int B, int N, int D, int64_t row_stri
     float* Fc = (float*)(ws + L.Fc);
     float* Fs = (float*)(ws + L.Fs);
     float* partial = (float*)(ws + L.partial);
+    if (L.fast) return spu_score_fft(x, B, N, D, row_stride, dt, sigma, use_hamming, partial, (float*)(ws + L.gpartial), L.n_tiles, scores, st);
     LUVC_LAUNCH("spu_tables", spu_tables, dim3((unsigned)((N + 255) / 256)), dim3(256), 0, st, N, sigma, use_hamming, tw, gk, gm);
     const int64_t total = (int64_t)B * N;
-    if (L.fast) {
-        const luvc_status rc = spu_score_fft(x, B, N, D, row_stride, dt, sigma, tw, gm, partial, L.n_tiles, st);
-        if (rc != LUVC_OK) return rc;
-        LUVC_LAUNCH("spu_finish", spu_finish, dim3((unsigned)((total + 63) / 64)), dim3(64 * kFinParts), 0, st, partial, N, L.n_tiles, total, scores);
-        return check_launch("spu score");
-    }
     const dim3 gf((unsigned)L.n_tiles, (unsigned)((sigma + 1 + 4 * kKPW - 1) / (4 * kKPW)), (unsigned)B);
     if (dt == LUVC_F32)
         LUVC_LAUNCH("spu_fwd_dense", (spu_fwd_dense<float>), gf, dim3(256), 0, st, (const float*)x, N, D, row_stride, sigma, tw, Fc, Fs);

@@ -72,6 +72,7 @@ def test_spu_full(oracle, i):
     code = lv.LUVC_BF16 if w.dtype == "bf16" else lv.LUVC_F32
     ws = torch.empty(lv.luvc_spu_workspace_bytes(w.spu_B, w.spu_N, w.spu_D, code, w.sigma), dtype=torch.uint8, device="cuda")
     scores = torch.empty((w.spu_B, w.spu_N), dtype=torch.float32, device="cuda")
+    ws.fill_(0xFF)                                                               # scratch contents must not matter
     lv.luvc_spu_score(xd, w.sigma, True, workspace=ws, out=scores)
     pr = lv.luvc_spu_prune(xd, scores, w.n_keep)
     torch.cuda.synchronize()

@@ -59,6 +59,31 @@ def test_score_strided_rows(oracle):
     score_case(oracle, xf, "f32", 9, False, "strided-fft-f32", stride_pad=3)
 
 
+def test_score_repeated_calls_with_poisoned_workspace(oracle):
+    """The per-sample completion counters and the cross-workgroup hand-over of the tile energies: many calls
+    in a row on one workspace that is overwritten with NaN patterns before each call must reproduce the
+    first result bit for bit (a stale or early read would return NaN or another call's values)."""
+    rng = np.random.default_rng(77)
+    shapes = [(3, 1024, 200, 102), (5, 720, 130, 54), (2, 2048, 96, 40)]
+    for B, N, D, sigma in shapes:
+        xa = wl.cast_io(rng.standard_normal((B, N, D)).astype(np.float32), "bf16")
+        xb = wl.cast_io(rng.standard_normal((B, N, D)).astype(np.float32), "bf16")
+        _, want_a, _ = score_case(oracle, xa, "bf16", sigma, True, "repeat-a")
+        _, want_b, _ = score_case(oracle, xb, "bf16", sigma, True, "repeat-b")
+        da, db = to_dev(xa, "bf16"), to_dev(xb, "bf16")
+        ws = torch.empty(lv.luvc_spu_workspace_bytes(B, N, D, lv.LUVC_BF16, sigma), dtype=torch.uint8, device="cuda")
+        out = torch.empty((B, N), dtype=torch.float32, device="cuda")
+        bad = torch.zeros((), dtype=torch.int64, device="cuda")
+        for it in range(40):
+            for d, want in ((da, want_a), (db, want_b)):
+                ws.fill_(0xFF)
+                out.fill_(float("nan"))
+                lv.luvc_spu_score(d, sigma, True, workspace=ws, out=out)
+                bad += (out.view(torch.int32) != want.view(torch.int32)).sum()
+        torch.cuda.synchronize()
+        assert bad.item() == 0, (B, N, D, sigma, bad.item())
+
+
 def test_score_special_signals(oracle):
     N, D = 64, 64
     n = np.arange(N)
@@ -103,7 +128,8 @@ def adversarial_scores(N, rng):
     return np.stack(cases)
 
 
-@pytest.mark.parametrize("N,k", [(1, 1), (7, 3), (64, 64), (257, 1), (1024, 205), (2048, 205), (3000, 1500), (720, 108)])
+@pytest.mark.parametrize("N,k", [(1, 1), (7, 3), (64, 64), (257, 1), (1024, 205), (2048, 205), (3000, 1500), (720, 108),
+                                 (4096, 4095), (4097, 33), (9000, 1000)])     # above 4096 tokens: selection and gather as two launches
 def test_select_against_stable_sort(oracle, N, k):
     rng = np.random.default_rng(N + k)
     sc = adversarial_scores(N, rng)
