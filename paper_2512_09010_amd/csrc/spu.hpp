@@ -21,7 +21,6 @@ luvc_status spu_score_dense(const void* x, int B, int N, int D, int64_t row_stri
 bool spu_fft_supported(int N, int sigma);
 luvc_status spu_score_fft(const void* x, int B, int N, int D, int64_t row_stride, luvc_dtype dt, int sigma, int use_hamming,
                           float* partial, float* gpartial, int n_tiles, float* scores, hipStream_t st);
-int spu_fft_groups(int n_tiles);      // tile groups per sample: gpartial holds [B, groups, N] floats
 
 luvc_status spu_prune_run(const void* x, const float* scores, int B, int N, int D, int64_t row_stride, luvc_dtype dt,
                           int n_keep, int32_t* kept_idx, void* x_out, hipStream_t st);

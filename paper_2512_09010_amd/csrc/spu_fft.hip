@@ -18,10 +18,9 @@
 // threads hold 16 points each for the radix-16 side, all 16 hold Q points each for the other side.
 // The pass-band accumulators F stay in registers across the N2 subsequences, so x is read exactly
 // once and nothing but N floats per tile is written.
-#include <atomic>
-
 #include "common.hpp"
 #include "spu.hpp"
+#include "spu_tiles.hpp"
 
 namespace luvc {
 
@@ -175,7 +174,6 @@ template <> struct pair_io<float> {
 };
 
 constexpr int kPairs = 16;                       // channel pairs per workgroup
-constexpr int kTileGroup = 8;                    // channel tiles whose energies are added in one go
 constexpr int kRowPad = 16 * kPairs + kPairs;    // float2 per exchange row: 16 x 16 pairs + one pad group
 
 // sum over the 16 lanes of a DPP row; every lane of the row ends up with the total, fixed order
@@ -190,8 +188,11 @@ __device__ __forceinline__ float row16_sum(float v)
 
 }  // namespace
 
+#ifndef LUVC_FFT_WAVES
+#define LUVC_FFT_WAVES 2
+#endif
 template <typename T, int Q, bool POW2, bool ALIGNED>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(LUVC_FFT_WAVES)))
 spu_fft16q(const T* __restrict__ x, int N, int D, int64_t row_stride, int sigma, int use_hamming,
            float* __restrict__ partial /* [B, n_tiles, N] */, float* __restrict__ gpartial /* [B, n_groups, N] */,
            unsigned int* __restrict__ done /* [B][1 + n_groups], zero between calls */, float* __restrict__ scores /* [B, N] */)
@@ -204,7 +205,7 @@ spu_fft16q(const T* __restrict__ x, int N, int D, int64_t row_stride, int sigma,
     float2* tw1 = tw + N;                        // [N1]   (cos, sin)(2 pi i / N1)
     float* eperm = reinterpret_cast<float*>(tw1 + N1);      // [N2][Q t][16 j] energies of this tile
     float* gm = eperm + N;                       // [sigma + 1]  M[f] / N  (Eq. 5 with the 1/N of Eq. 7)
-    __shared__ bool is_last;
+    __shared__ int is_last;
     const int tid = threadIdx.x, c = tid & 15, t = tid >> 4;
     // neighbouring channel tiles share 128-byte lines of every token row: keep them on one XCD
     const int n_tiles = gridDim.x;
@@ -229,20 +230,21 @@ spu_fft16q(const T* __restrict__ x, int N, int D, int64_t row_stride, int sigma,
 #pragma unroll
     for (int kb = 0; kb < Q; ++kb) {
         const int k1 = t + 16 * kb;
-        kpos[kb] = k1 <= sigma ? k1 : N - N1 + k1;        // k mod N (bins outside the band are masked later)
-        ph[kb] = 0;                                        // (k * n2) mod N
+        kpos[kb] = 8 * (k1 <= sigma ? k1 : N - N1 + k1);  // k mod N (bins outside the band are masked later), as a byte offset into tw
+        ph[kb] = 0;                                        // (k * n2) mod N, likewise
         F[kb] = {0.f, 0.f};
     }
-    auto advance = [&](int kb) {
-        ph[kb] += kpos[kb];
-        if (POW2) ph[kb] &= N - 1;
-        else if (ph[kb] >= N) ph[kb] -= N;
-    };
-    auto step1 = [&](int e) {                    // (e + t) mod N1
-        e += t;
-        if (Q == 16) e &= N1 - 1;
-        else if (e >= N1) e -= N1;
-        return e;
+    // W_N^{+-k n2} for bin kb of this thread: a power-of-two N takes the product modulo N directly, any
+    // other N keeps the running sum
+    auto tw_k = [&](int kb, int n2) {
+        int off;
+        if (POW2) off = (int)__umul24((unsigned)kpos[kb], (unsigned)n2) & (8 * N - 1);
+        else {
+            off = ph[kb];
+            ph[kb] += kpos[kb];
+            if (ph[kb] >= 8 * N) ph[kb] -= 8 * N;
+        }
+        return *reinterpret_cast<const float2*>(reinterpret_cast<const char*>(tw) + off);
     };
 
     typename pio::raw_t raw[16];
@@ -276,8 +278,35 @@ spu_fft16q(const T* __restrict__ x, int N, int D, int64_t row_stride, int sigma,
         }
     }
     __syncthreads();
-    if (tid < N1) tw1[tid] = tw[tid * N2];
-    __syncthreads();                             // twiddle tables ready
+    // W_N1^{t i}, i < 16: the twiddles between the two passes of every N1-point transform, both directions
+#ifndef LUVC_FFT_HOIST
+#define LUVC_FFT_HOIST 1
+#endif
+    constexpr bool kHoist = LUVC_FFT_HOIST == 2 || (LUVC_FFT_HOIST == 1 && Q == 16);
+    cf w1[16];
+    if (kHoist) {
+        int e1 = 0;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const float2 w = tw[e1 * N2];
+            w1[i] = {w.x, w.y};
+            e1 += t;
+            if (e1 >= N1) e1 -= N1;
+        }
+    }
+    else {
+        if (tid < N1) tw1[tid] = tw[tid * N2];
+        __syncthreads();
+    }
+    // without the register copy: walk the N1 table, i = 0, 1, 2, ... in order (o1 = t i mod N1)
+    int o1 = 0;
+    auto tw1_next = [&](int i) {
+        if (kHoist) return w1[i];
+        const float2 w = tw1[o1];
+        o1 += t;
+        if (o1 >= N1) o1 -= N1;
+        return cf{w.x, w.y};
+    };
 
     // ------------------------------------------------------------------ forward (Eq. 4 on the pass band)
     for (int n2 = 0; n2 < N2; ++n2) {
@@ -287,12 +316,10 @@ spu_fft16q(const T* __restrict__ x, int N, int D, int64_t row_stride, int sigma,
         if (n2 + 1 < N2) load_sub(n2 + 1);       // next subsequence in flight while this one is transformed
         if (rdx) {
             fft16<false>(v);                     // over j -> ka
-            int e1 = 0;
+            o1 = 0;
 #pragma unroll
             for (int ka = 0; ka < 16; ++ka) {
-                const float2 w = tw1[e1];
-                e1 = step1(e1);
-                const cf r = cmulc(v[ka], cf{w.x, w.y});   // * W_N1^{t ka}
+                const cf r = cmulc(v[ka], tw1_next(ka));         // * W_N1^{t ka}
                 xbuf[ka * kRowPad + t * kPairs + c] = make_float2(r.x, r.y);
             }
         }
@@ -304,9 +331,8 @@ spu_fft16q(const T* __restrict__ x, int N, int D, int64_t row_stride, int sigma,
         dftq<Q, false>::run(u);                  // over the residue -> kb ; u[kb] = Y[t + 16 kb]
 #pragma unroll
         for (int kb = 0; kb < Q; ++kb) {
-            const float2 w = tw[ph[kb]];
+            const float2 w = tw_k(kb, n2);
             F[kb] = F[kb] + cmulc(u[kb], cf{w.x, w.y});    // * W_N^{k n2}
-            advance(kb);
         }
     }
     // ------------------------------------------------------------------ mask (Eq. 5-6) with the 1/N of Eq. 7
@@ -323,17 +349,14 @@ spu_fft16q(const T* __restrict__ x, int N, int D, int64_t row_stride, int sigma,
         cf u[Q];
 #pragma unroll
         for (int kb = 0; kb < Q; ++kb) {
-            const float2 w = tw[ph[kb]];
+            const float2 w = tw_k(kb, n2);
             u[kb] = cmul(F[kb], cf{w.x, w.y});   // F[k] W_N^{-k n2}
-            advance(kb);
         }
         dftq<Q, true>::run(u);                   // over kb -> residue s
-        int e1 = 0;
+        o1 = 0;
 #pragma unroll
         for (int s = 0; s < Q; ++s) {
-            const float2 w = tw1[e1];
-            e1 = step1(e1);
-            const cf r = cmul(u[s], cf{w.x, w.y});         // * W_N1^{-s ka}
+            const cf r = cmul(u[s], tw1_next(s));               // * W_N1^{-s ka}
             xbuf[s * kRowPad + t * kPairs + c] = make_float2(r.x, r.y);
         }
         __syncthreads();
@@ -353,68 +376,15 @@ spu_fft16q(const T* __restrict__ x, int N, int D, int64_t row_stride, int sigma,
         }
         __syncthreads();
     }
-    // The tile's energies go out as device-scope (write-through) stores and are read back below with
-    // device-scope loads: the other workgroups of the sample run on other XCDs, whose L2s are not kept
-    // coherent with this one, and a full release / acquire fence (an L2 write-back and invalidate per
-    // workgroup) costs more than the whole transform.
-    unsigned int* pout = reinterpret_cast<unsigned int*>(partial + ((int64_t)b * n_tiles + tile) * N);
+    float* pout = partial + ((int64_t)b * n_tiles + tile) * N;
     for (int n = tid; n < N; n += 256) {         // n = N2 (Q j + t') + n2
         const int n2 = POW2 ? (n & (N2 - 1)) : n % N2;
         const int q = (n - n2) / N2;
         const int tq = Q == 16 ? (q & 15) : q % Q, j = Q == 16 ? (q >> 4) : q / Q;
-        __hip_atomic_store(pout + n, __float_as_uint(eperm[(n2 * Q + tq) * 16 + j]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        tile_store(pout + n, eperm[(n2 * Q + tq) * 16 + j]);
     }
     // ------------------------------------------------------------------ Eq. 8 across the channel tiles
-    // Two levels, both in index order so that the result does not depend on which workgroup does the
-    // adding: the workgroup that completes a group of kTileGroup tiles last adds those tiles; the one
-    // that completes the last group of the sample adds the groups and takes the square root.  Every
-    // counter wraps back to zero.
-    const int n_groups = (n_tiles + kTileGroup - 1) / kTileGroup;
-    const int grp = tile / kTileGroup, t_first = grp * kTileGroup;
-    const int t_cnt = n_tiles - t_first < kTileGroup ? n_tiles - t_first : kTileGroup;
-    unsigned int* cnt = done + (int64_t)b * (n_groups + 1);
-    const int nh = N >> 1;                       // 2 divides N
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");       // this wavefront's stores have been performed
-    __syncthreads();
-    if (tid == 0) is_last = atomicInc(cnt + 1 + grp, (unsigned)t_cnt - 1u) == (unsigned)t_cnt - 1u;
-    __syncthreads();
-    if (!is_last) return;
-    {
-        const unsigned long long* pin = reinterpret_cast<const unsigned long long*>(partial + ((int64_t)b * n_tiles + t_first) * N);
-        unsigned long long* gout = reinterpret_cast<unsigned long long*>(gpartial + ((int64_t)b * n_groups + grp) * N);
-        for (int i = tid; i < nh; i += 256) {
-            unsigned long long p[kTileGroup];
-#pragma unroll
-            for (int tl = 0; tl < kTileGroup; ++tl)
-                p[tl] = tl < t_cnt ? __hip_atomic_load(pin + (int64_t)tl * nh + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0ull;
-            double e0 = 0.0, e1 = 0.0;
-#pragma unroll
-            for (int tl = 0; tl < kTileGroup; ++tl) {
-                e0 += (double)__uint_as_float((unsigned int)p[tl]);
-                e1 += (double)__uint_as_float((unsigned int)(p[tl] >> 32));
-            }
-            const unsigned long long r = (unsigned long long)__float_as_uint((float)e0) | ((unsigned long long)__float_as_uint((float)e1) << 32);
-            __hip_atomic_store(gout + i, r, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-    }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();                             // also: every thread has read is_last
-    if (tid == 0) is_last = atomicInc(cnt, (unsigned)n_groups - 1u) == (unsigned)n_groups - 1u;
-    __syncthreads();
-    if (!is_last) return;
-    const unsigned long long* gin = reinterpret_cast<const unsigned long long*>(gpartial + (int64_t)b * n_groups * N);
-    for (int i = tid; i < nh; i += 256) {
-        double e0 = 0.0, e1 = 0.0;
-#pragma unroll 8
-        for (int gi = 0; gi < n_groups; ++gi) {
-            const unsigned long long p = __hip_atomic_load(gin + (int64_t)gi * nh + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            e0 += (double)__uint_as_float((unsigned int)p);
-            e1 += (double)__uint_as_float((unsigned int)(p >> 32));
-        }
-        float* so = scores + (int64_t)b * N + 2 * i;
-        so[0] = (float)sqrt(e0);
-        so[1] = (float)sqrt(e1);
-    }
+    tiles_to_scores<256, 4>(partial, gpartial, done, scores, b, tile, n_tiles, N, &is_last);
 }
 
 static size_t fft_lds_bytes(int N, int Q, int sigma)
@@ -435,15 +405,6 @@ static int fft_pick_q(int N, int sigma)
 
 bool spu_fft_supported(int N, int sigma) { return fft_pick_q(N, sigma) != 0; }
 
-// Completion counters of the samples in flight (one per sample and one per tile group of a sample), one
-// set per call slot.  They are zero whenever no call that uses the slot is running: the workgroup that
-// finds a counter complete wraps it back to zero.
-constexpr int kSlotCounters = 16384, kSlots = 64;
-__device__ unsigned int g_fft_done[kSlots * kSlotCounters];
-static std::atomic<unsigned> g_fft_slot{0};
-
-int spu_fft_groups(int n_tiles) { return (n_tiles + kTileGroup - 1) / kTileGroup; }
-
 luvc_status spu_score_fft(const void* x, int B, int N, int D, int64_t row_stride, luvc_dtype dt, int sigma, int use_hamming,
                           float* partial, float* gpartial, int n_tiles, float* scores, hipStream_t st)
 {
@@ -453,11 +414,9 @@ luvc_status spu_score_fft(const void* x, int B, int N, int D, int64_t row_stride
     // channel pairs are fetched with one access when every pair is naturally aligned
     const size_t es = dt == LUVC_F32 ? 4 : 2;
     const bool aligned = (row_stride % 2 == 0) && ((uintptr_t)x % (2 * es) == 0) && (D % 2 == 0);
-    const int n_groups = spu_fft_groups(n_tiles);
+    const int n_groups = spu_tile_groups(n_tiles);
     if (n_groups + 1 > kSlotCounters) { set_error("D=%d exceeds the supported width of the fft path", D); return LUVC_ERR_UNSUPPORTED; }
     const int per_launch = kSlotCounters / (n_groups + 1);       // samples whose counters fit one slot
-    unsigned int* done_base = nullptr;
-    if (hipGetSymbolAddress((void**)&done_base, HIP_SYMBOL(g_fft_done)) != hipSuccess) return check_launch("spu score (counters)");
 #define LUVC_FFT(TT, QQ, P2, AL) LUVC_LAUNCH("spu_fft", (spu_fft16q<TT, QQ, P2, AL>), grid, dim3(256), lds, st, (const TT*)xs, N, D, row_stride, sigma, use_hamming, ps, gs, done, ss)
 #define LUVC_FFT_A(TT, QQ, P2) do { if (aligned) LUVC_FFT(TT, QQ, P2, true); else LUVC_FFT(TT, QQ, P2, false); } while (0)
 #define LUVC_FFT_T(TT) do { if (Q == 16) { if (pow2) LUVC_FFT_A(TT, 16, true); else LUVC_FFT_A(TT, 16, false); } \
@@ -469,7 +428,8 @@ luvc_status spu_score_fft(const void* x, int B, int N, int D, int64_t row_stride
         float* ps = partial + (size_t)b0 * n_tiles * N;
         float* gs = gpartial + (size_t)b0 * n_groups * N;
         float* ss = scores + (size_t)b0 * N;
-        unsigned int* done = done_base + (size_t)(g_fft_slot.fetch_add(1) % kSlots) * kSlotCounters;
+        unsigned int* done = spu_take_counters();
+        if (!done) return LUVC_ERR_HIP;
         if (dt == LUVC_F32) LUVC_FFT_T(float); else LUVC_FFT_T(bf16_t);
     }
 #undef LUVC_FFT_T

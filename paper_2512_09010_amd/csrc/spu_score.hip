@@ -12,8 +12,13 @@
 //   spu_fwd_dense   C_k, S_k for a tile of 64 channels and a group of bins
 //   spu_inv_dense   x'[n] for a tile of 64 channels and a chunk of tokens, squared and summed over the tile
 //   spu_finish      fixed-order sum over channel tiles, square root (Eq. 8)
+//   spu_dense_fused all of the above in one launch, for samples whose tables and pass-band spectrum of a
+//                   64-channel tile fit in LDS (small N and sigma, where the launches themselves dominate)
+#include <atomic>
+
 #include "common.hpp"
 #include "spu.hpp"
+#include "spu_tiles.hpp"
 
 namespace luvc {
 
@@ -145,6 +150,135 @@ spu_finish(const float* __restrict__ partial, int N, int n_tiles, int64_t total,
     }
 }
 
+// ------------------------------------------------------------------ one launch for small samples
+// Workgroup (tile, b): 64 channels (lanes) x 16 wavefronts.  Forward: the wavefronts split the tokens
+// (n = wave, wave + 16, ...), each accumulates kDfBins bins at a time, the 16 partial sums of a bin meet
+// in LDS and are added in wavefront order into F = g_k (C_k, S_k).  Inverse: the wavefronts split the
+// tokens again, kDfTok tokens per register block; energies summed over the lanes; tiles summed by the
+// hand-over of spu_tiles.hpp.
+constexpr int kDfWaves = 16, kDfBins = 6, kDfTok = 4;
+
+static size_t dense_fused_lds(int N, int sigma)
+{
+    return sizeof(float2) * (size_t)N + sizeof(float) * ((size_t)(sigma + 1) * 128 + (size_t)(sigma + 1) + (size_t)kDfWaves * kDfBins * 128);
+}
+
+template <typename T>
+__global__ void __launch_bounds__(64 * kDfWaves)
+spu_dense_fused(const T* __restrict__ x, int N, int D, int64_t row_stride, int sigma, int use_hamming,
+                float* __restrict__ partial, float* __restrict__ gpartial, unsigned int* __restrict__ done,
+                float* __restrict__ scores)
+{
+    using tr = io_traits<T>;
+    extern __shared__ float2 dsm[];
+    float2* tw = dsm;                                               // [N]  (cos, sin)(2 pi i / N)
+    float* F = reinterpret_cast<float*>(tw + N);                    // [sigma + 1][2][64]  g_k C_k, g_k S_k
+    float* gk = F + (size_t)(sigma + 1) * 128;                      // [sigma + 1]
+    float* red = gk + (sigma + 1);                                  // [16][kDfBins][2][64]
+    __shared__ int flag;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int tile = blockIdx.x, n_tiles = gridDim.x, b = blockIdx.y;
+    const int d = tile * 64 + lane;
+    const bool live = d < D;
+    const T* xb = x + (int64_t)b * N * row_stride + (live ? d : 0);
+
+    for (int i = tid; i < N; i += 64 * kDfWaves) {
+        double sd, cd;
+        sincospi(2.0 * (double)i / (double)N, &sd, &cd);
+        tw[i] = make_float2((float)cd, (float)sd);
+    }
+    for (int k = tid; k <= sigma; k += 64 * kDfWaves) {
+        double w = 1.0;
+        if (use_hamming && N > 1) w = 0.54 + 0.46 * cospi(2.0 * (double)k / (double)(N - 1));
+        const double pair = (k == 0 || 2 * k == N) ? 1.0 : 2.0;       // +k and -k paired (real-signal form)
+        gk[k] = (float)(pair * w / (double)N);
+    }
+    __syncthreads();
+
+    // ---- forward (Eq. 4 on the pass band), mask (Eq. 5-6) with the 1/N of Eq. 7
+    for (int k0 = 0; k0 <= sigma; k0 += kDfBins) {
+        float ac[kDfBins], as[kDfBins];
+#pragma unroll
+        for (int j = 0; j < kDfBins; ++j) { ac[j] = 0.f; as[j] = 0.f; }
+#pragma unroll 4
+        for (int n = wave; n < N; n += kDfWaves) {
+            const float xv = live ? tr::load(xb + (int64_t)n * row_stride) : 0.f;
+            int idx = (int)(((int64_t)k0 * n) % N);                  // (k n) mod N, wave-uniform
+#pragma unroll
+            for (int j = 0; j < kDfBins; ++j) {
+                const float2 t = tw[idx];
+                ac[j] = fmaf(xv, t.x, ac[j]);
+                as[j] = fmaf(xv, t.y, as[j]);
+                idx += n;
+                if (idx >= N) idx -= N;
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < kDfBins; ++j) {
+            red[((wave * kDfBins + j) * 2 + 0) * 64 + lane] = ac[j];
+            red[((wave * kDfBins + j) * 2 + 1) * 64 + lane] = as[j];
+        }
+        __syncthreads();
+        for (int i = tid; i < kDfBins * 128; i += 64 * kDfWaves) {     // i = (j, cos/sin, lane)
+            const int k = k0 + (i >> 7);
+            if (k <= sigma) {
+                float sum = 0.f;
+#pragma unroll
+                for (int w = 0; w < kDfWaves; ++w) sum += red[w * kDfBins * 128 + i];
+                F[k * 128 + (i & 127)] = gk[k] * sum;
+            }
+        }
+        __syncthreads();
+    }
+
+    // ---- inverse (Eq. 7, +k and -k paired) and energy over the tile's channels (Eq. 8)
+    float* pout = partial + ((int64_t)b * n_tiles + tile) * N;
+    for (int nb = wave; nb < N; nb += kDfWaves * kDfTok) {
+        float acc[kDfTok];
+        int idx[kDfTok], stepn[kDfTok];
+#pragma unroll
+        for (int j = 0; j < kDfTok; ++j) {
+            const int n = nb + kDfWaves * j;
+            acc[j] = 0.f; idx[j] = 0; stepn[j] = n < N ? n : 0;
+        }
+        for (int k = 0; k <= sigma; ++k) {
+            const float c = F[k * 128 + lane], sn = F[k * 128 + 64 + lane];
+#pragma unroll
+            for (int j = 0; j < kDfTok; ++j) {
+                const float2 t = tw[idx[j]];
+                acc[j] = fmaf(c, t.x, acc[j]);
+                acc[j] = fmaf(sn, t.y, acc[j]);
+                idx[j] += stepn[j];
+                if (idx[j] >= N) idx[j] -= N;
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < kDfTok; ++j) {
+            const int n = nb + kDfWaves * j;
+            const float e = wave_sum(acc[j] * acc[j]);
+            if (lane == 0 && n < N) tile_store(pout + n, e);
+        }
+    }
+    tiles_to_scores<64 * kDfWaves, 1>(partial, gpartial, done, scores, b, tile, n_tiles, N, &flag);
+}
+
+// Completion counters of the samples in flight (one per sample and one per tile group of a sample), one
+// set per call slot.  They are zero whenever no call that uses the slot is running (see spu_tiles.hpp).
+constexpr int kSlots = 64;
+__device__ unsigned int g_spu_done[kSlots * kSlotCounters];
+static std::atomic<unsigned> g_spu_slot{0};
+
+unsigned int* spu_take_counters()
+{
+    unsigned int* base = nullptr;
+    if (hipGetSymbolAddress((void**)&base, HIP_SYMBOL(g_spu_done)) != hipSuccess) {
+        check_launch("spu score (counters)");
+        return nullptr;
+    }
+    return base + (size_t)(g_spu_slot.fetch_add(1) % kSlots) * kSlotCounters;
+}
+
 // ------------------------------------------------------------------ host side
 SpuLayout spu_layout(int B, int N, int D, int sigma)
 {
@@ -160,7 +294,7 @@ SpuLayout spu_layout(int B, int N, int D, int sigma)
     L.Fc = off;      off += align_up(sizeof(float) * spec);
     L.Fs = off;      off += align_up(sizeof(float) * spec);
     L.partial = off; off += align_up(sizeof(float) * (size_t)B * L.n_tiles * N);
-    L.gpartial = off; off += L.fast ? align_up(sizeof(float) * (size_t)B * spu_fft_groups(L.n_tiles) * N) : 0;
+    L.gpartial = off; off += align_up(sizeof(float) * (size_t)B * spu_tile_groups(L.n_tiles) * N);
     L.bytes = off;
     return L;
 }
@@ -177,6 +311,26 @@ luvc_status spu_score_dense(const void* x, int B, int N, int D, int64_t row_stri
     float* Fs = (float*)(ws + L.Fs);
     float* partial = (float*)(ws + L.partial);
     if (L.fast) return spu_score_fft(x, B, N, D, row_stride, dt, sigma, use_hamming, partial, (float*)(ws + L.gpartial), L.n_tiles, scores, st);
+    if (dense_fused_lds(N, sigma) <= 64 * 1024 && spu_tile_groups(L.n_tiles) + 1 <= kSlotCounters) {
+        const int per_launch = kSlotCounters / (spu_tile_groups(L.n_tiles) + 1);
+        const size_t es = dt == LUVC_F32 ? 4 : 2;
+        for (int b0 = 0; b0 < B; b0 += per_launch) {
+            const int nb = B - b0 < per_launch ? B - b0 : per_launch;
+            const dim3 grid((unsigned)L.n_tiles, (unsigned)nb);
+            const char* xs = (const char*)x + (size_t)b0 * N * row_stride * es;
+            float* ps = partial + (size_t)b0 * L.n_tiles * N;
+            float* gs = (float*)(ws + L.gpartial) + (size_t)b0 * spu_tile_groups(L.n_tiles) * N;
+            unsigned int* done = spu_take_counters();
+            if (!done) return LUVC_ERR_HIP;
+            if (dt == LUVC_F32)
+                LUVC_LAUNCH("spu_dense_fused", (spu_dense_fused<float>), grid, dim3(64 * kDfWaves), dense_fused_lds(N, sigma), st,
+                            (const float*)xs, N, D, row_stride, sigma, use_hamming, ps, gs, done, scores + (size_t)b0 * N);
+            else
+                LUVC_LAUNCH("spu_dense_fused", (spu_dense_fused<bf16_t>), grid, dim3(64 * kDfWaves), dense_fused_lds(N, sigma), st,
+                            (const bf16_t*)xs, N, D, row_stride, sigma, use_hamming, ps, gs, done, scores + (size_t)b0 * N);
+        }
+        return check_launch("spu score (dense, one launch)");
+    }
     LUVC_LAUNCH("spu_tables", spu_tables, dim3((unsigned)((N + 255) / 256)), dim3(256), 0, st, N, sigma, use_hamming, tw, gk, gm);
     const int64_t total = (int64_t)B * N;
     const dim3 gf((unsigned)L.n_tiles, (unsigned)((sigma + 1 + 4 * kKPW - 1) / (4 * kKPW)), (unsigned)B);
