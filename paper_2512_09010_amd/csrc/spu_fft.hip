@@ -417,7 +417,7 @@ luvc_status spu_score_fft(const void* x, int B, int N, int D, int64_t row_stride
     const int n_groups = spu_tile_groups(n_tiles);
     if (n_groups + 1 > kSlotCounters) { set_error("D=%d exceeds the supported width of the fft path", D); return LUVC_ERR_UNSUPPORTED; }
     const int per_launch = kSlotCounters / (n_groups + 1);       // samples whose counters fit one slot
-#define LUVC_FFT(TT, QQ, P2, AL) LUVC_LAUNCH("spu_fft", (spu_fft16q<TT, QQ, P2, AL>), grid, dim3(256), lds, st, (const TT*)xs, N, D, row_stride, sigma, use_hamming, ps, gs, done, ss)
+#define LUVC_FFT(TT, QQ, P2, AL) LUVC_LAUNCH("spu_fft16q", (spu_fft16q<TT, QQ, P2, AL>), grid, dim3(256), lds, st, (const TT*)xs, N, D, row_stride, sigma, use_hamming, ps, gs, done, ss)
 #define LUVC_FFT_A(TT, QQ, P2) do { if (aligned) LUVC_FFT(TT, QQ, P2, true); else LUVC_FFT(TT, QQ, P2, false); } while (0)
 #define LUVC_FFT_T(TT) do { if (Q == 16) { if (pow2) LUVC_FFT_A(TT, 16, true); else LUVC_FFT_A(TT, 16, false); } \
                             else if (Q == 15) LUVC_FFT_A(TT, 15, false); else LUVC_FFT_A(TT, 9, false); } while (0)
