@@ -125,7 +125,11 @@ size_t luvc_spu_workspace_bytes(int B, int N, int D, luvc_dtype dtype, int sigma
  *   row_stride  elements between consecutive tokens, >= D
  *   sigma       cut-off, 0 <= sigma <= N/2
  *   scores      device [B,N] fp32
- * Arithmetic is fp32 (bf16 is a storage type only).
+ * Arithmetic is fp32 (bf16 is a storage type only).  The sum over channels is taken in a fixed order:
+ * the same input gives the same bits on every call.
+ * Concurrency: calls may overlap on different streams as long as each has its own workspace and at most
+ * 64 of them are in flight on one GPU (the single-launch kernels keep per-sample completion counters in
+ * a static device array that is handed out in 64 slots).
  */
 luvc_status luvc_spu_score(const void* x, int B, int N, int D, int64_t row_stride, luvc_dtype dtype,
                            int sigma, int use_hamming, float* scores,
