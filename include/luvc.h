@@ -109,6 +109,25 @@ luvc_status luvc_oim_merge(const void* x, const int32_t* sizes_in,
                            void* x_out, int32_t* sizes_out, int32_t* merged_map, int32_t* kept_map,
                            void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/*
+ * OIM with a wider candidate set (the bipartite matching behind the similarity cost O(n_v^1.5 k)
+ * of Section 3.1; the appendix "Iterative Strategy and Pseudocode of OIM" runs it with a merge
+ * number of 2): as luvc_oim_merge, except that a source at position a of a line considers every
+ * destination b of the line with |b - a| <= 2 * radius - 1, or every destination of the line when
+ * radius = 0; a destination can then absorb several sources (size-weighted mean over all of them,
+ * added in ascending position).  radius = 1 is luvc_oim_merge itself.
+ * The source x destination dot products of every line are evaluated in fp64 on the matrix cores.
+ * Limits: lines of at most 2048 tokens when radius != 1.
+ * Workspace: luvc_oim_wide_workspace_bytes for the same arguments.
+ */
+size_t luvc_oim_wide_workspace_bytes(int B, int H, int W, int D, luvc_dtype dtype,
+                                     const luvc_oim_pass* passes, int n_passes, int radius);
+luvc_status luvc_oim_merge_wide(const void* x, const int32_t* sizes_in,
+                                int B, int H, int W, int D, luvc_dtype dtype,
+                                const luvc_oim_pass* passes, int n_passes, int radius, int64_t target_tokens,
+                                void* x_out, int32_t* sizes_out, int32_t* merged_map, int32_t* kept_map,
+                                void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Bytes of workspace luvc_spu_score needs (0 on invalid arguments). */
 size_t luvc_spu_workspace_bytes(int B, int N, int D, luvc_dtype dtype, int sigma);
 

@@ -17,7 +17,7 @@ LUVC_OK, LUVC_ERR_INVALID_ARG, LUVC_ERR_UNSUPPORTED, LUVC_ERR_WORKSPACE, LUVC_ER
 LUVC_F32, LUVC_BF16 = 0, 1
 
 EXPORTS = ("luvc_version", "luvc_last_error", "luvc_oim_plan", "luvc_oim_workspace_bytes", "luvc_oim_merge",
-           "luvc_spu_workspace_bytes", "luvc_spu_score", "luvc_keep_count", "luvc_spu_prune",
+           "luvc_oim_wide_workspace_bytes", "luvc_oim_merge_wide", "luvc_spu_workspace_bytes", "luvc_spu_score", "luvc_keep_count", "luvc_spu_prune",
            "luvc_profile_start", "luvc_profile_stop", "luvc_profile_kernel")
 
 
@@ -53,6 +53,10 @@ def lib() -> ctypes.CDLL:
     L.luvc_oim_workspace_bytes.restype = sz
     L.luvc_oim_merge.argtypes = [vp, vp, i, i, i, i, i, pp, i, i64, vp, vp, vp, vp, vp, sz, vp]
     L.luvc_oim_merge.restype = i
+    L.luvc_oim_wide_workspace_bytes.argtypes = [i, i, i, i, i, pp, i, i]
+    L.luvc_oim_wide_workspace_bytes.restype = sz
+    L.luvc_oim_merge_wide.argtypes = [vp, vp, i, i, i, i, i, pp, i, i, i64, vp, vp, vp, vp, vp, sz, vp]
+    L.luvc_oim_merge_wide.restype = i
     L.luvc_spu_workspace_bytes.argtypes = [i, i, i, i, i]
     L.luvc_spu_workspace_bytes.restype = sz
     L.luvc_spu_score.argtypes = [vp, i, i, i, i64, i, i, i, vp, vp, sz, vp]
@@ -158,6 +162,37 @@ def luvc_oim_merge(x, passes, sizes=None, target_tokens: int = 0, want_maps: boo
     _check(lib().luvc_oim_merge(_ptr(x), _ptr(sizes), B, H, W, D, code, parr, len(passes), int(target_tokens),
                                 _ptr(out["x"]), _ptr(out["sizes"]), _ptr(out.get("merged_map")), _ptr(out.get("kept_map")),
                                 _ptr(workspace), workspace.numel(), _stream(stream)))
+    return out
+
+
+def luvc_oim_wide_workspace_bytes(B, H, W, D, dtype_code, passes, radius) -> int:
+    return lib().luvc_oim_wide_workspace_bytes(B, H, W, D, dtype_code, _passes(passes), len(passes), int(radius))
+
+
+def luvc_oim_merge_wide(x, passes, radius: int, sizes=None, target_tokens: int = 0, want_maps: bool = True, workspace=None,
+                        stream=None, out=None):
+    """As luvc_oim_merge with candidates within `radius` (0 = the whole line).  Returns dict(x, sizes, merged_map, kept_map)."""
+    import torch
+    assert x.is_cuda and x.is_contiguous() and x.dim() == 4
+    B, H, W, D = x.shape
+    code = _dtype_code(x)
+    parr = _passes(passes)
+    Ho, Wo = out_grid(H, W, passes)
+    need = lib().luvc_oim_wide_workspace_bytes(B, H, W, D, code, parr, len(passes), int(radius))
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=x.device)
+    if out is None:
+        out = dict(
+            x=torch.empty((B, max(Ho, 0), max(Wo, 0), D), dtype=x.dtype, device=x.device),
+            sizes=torch.empty((B, max(Ho, 0), max(Wo, 0)), dtype=torch.int32, device=x.device),
+            merged_map=torch.empty((B, H * W), dtype=torch.int32, device=x.device) if want_maps else None,
+            kept_map=torch.empty((B, max(Ho, 0) * max(Wo, 0)), dtype=torch.int32, device=x.device) if want_maps else None,
+        )
+    if sizes is not None:
+        assert sizes.is_cuda and sizes.dtype == torch.int32 and sizes.is_contiguous() and sizes.numel() == B * H * W
+    _check(lib().luvc_oim_merge_wide(_ptr(x), _ptr(sizes), B, H, W, D, code, parr, len(passes), int(radius), int(target_tokens),
+                                     _ptr(out["x"]), _ptr(out["sizes"]), _ptr(out.get("merged_map")), _ptr(out.get("kept_map")),
+                                     _ptr(workspace), workspace.numel(), _stream(stream)))
     return out
 
 

@@ -80,10 +80,10 @@ static bool walk_schedule(int B, int H, int W, int D, const luvc_oim_pass* passe
 }
 
 struct OimLayout {
-    size_t xbuf[2], sbuf[2], kbuf[2], maps[kMaxPasses], n2, dn, anchor, absorb, bytes;
+    size_t xbuf[2], sbuf[2], kbuf[2], maps[kMaxPasses], n2, dn, anchor, absorb, gram, srcdest, bytes;
 };
 
-static OimLayout oim_layout(int B, int D, luvc_dtype dt, const OimPlan& pl)
+static OimLayout oim_layout(int B, int D, luvc_dtype dt, const OimPlan& pl, const luvc_oim_pass* passes = nullptr, int radius = 1)
 {
     OimLayout L{};
     size_t off = 0;
@@ -109,6 +109,16 @@ static OimLayout oim_layout(int B, int D, luvc_dtype dt, const OimPlan& pl)
     L.dn = off;     off += align_up(max_in * sizeof(double));
     L.anchor = off; off += align_up(max_out * sizeof(int32_t));
     L.absorb = off; off += align_up(max_out * sizeof(int32_t));
+    // wide matching: the largest source x destination matrix set and merge list of any pass
+    size_t gram = 0, srcdest = 0;
+    if (radius != 1 && passes)
+        for (int i = 0; i < pl.n; ++i) {
+            const size_t gb = oim_wide_gram_bytes(B, pl.h[i], pl.w[i], passes[i].axis), sb = oim_wide_srcdest_bytes(B, pl.h[i], pl.w[i], passes[i].axis);
+            if (gb > gram) gram = gb;
+            if (sb > srcdest) srcdest = sb;
+        }
+    L.gram = off;    off += align_up(gram);
+    L.srcdest = off; off += align_up(srcdest);
     L.bytes = off;
     return L;
 }
@@ -193,10 +203,10 @@ size_t luvc_oim_workspace_bytes(int B, int H, int W, int D, luvc_dtype dtype, co
     return oim_layout(B, D, dtype, pl).bytes;
 }
 
-luvc_status luvc_oim_merge(const void* x, const int32_t* sizes_in, int B, int H, int W, int D, luvc_dtype dtype,
-                           const luvc_oim_pass* passes, int n_passes, int64_t target_tokens,
-                           void* x_out, int32_t* sizes_out, int32_t* merged_map, int32_t* kept_map,
-                           void* workspace, size_t workspace_bytes, void* hip_stream)
+static luvc_status oim_merge_impl(const void* x, const int32_t* sizes_in, int B, int H, int W, int D, luvc_dtype dtype,
+                                  const luvc_oim_pass* passes, int n_passes, int radius, int64_t target_tokens,
+                                  void* x_out, int32_t* sizes_out, int32_t* merged_map, int32_t* kept_map,
+                                  void* workspace, size_t workspace_bytes, void* hip_stream)
 {
     if (!dtype_ok(dtype)) { set_error("unknown dtype %d", (int)dtype); return LUVC_ERR_INVALID_ARG; }
     if (!x || !x_out || !sizes_out) { set_error("x, x_out and sizes_out must not be NULL"); return LUVC_ERR_INVALID_ARG; }
@@ -207,7 +217,14 @@ luvc_status luvc_oim_merge(const void* x, const int32_t* sizes_in, int B, int H,
         set_error("schedule ends at %dx%d = %lld tokens, target is %lld", Ho, Wo, (long long)Ho * Wo, (long long)target_tokens);
         return LUVC_ERR_INVALID_ARG;
     }
-    const OimLayout L = oim_layout(B, D, dtype, pl);
+    if (radius < 0) { set_error("radius must be 0 (whole line) or positive"); return LUVC_ERR_INVALID_ARG; }
+    if (radius != 1)
+        for (int i = 0; i < pl.n; ++i)
+            if ((passes[i].axis ? pl.w[i] : pl.h[i]) > kMaxWideLineLen) {
+                set_error("pass %d: wide matching supports lines of at most %d tokens", i, kMaxWideLineLen);
+                return LUVC_ERR_UNSUPPORTED;
+            }
+    const OimLayout L = oim_layout(B, D, dtype, pl, passes, radius);
     if (!workspace_ok(workspace, workspace_bytes, L.bytes)) return LUVC_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)hip_stream;
     char* ws = (char*)workspace;
@@ -229,7 +246,7 @@ luvc_status luvc_oim_merge(const void* x, const int32_t* sizes_in, int B, int H,
     Step steps[kMaxPasses];
     int n_steps = 0;
     for (int i = 0; i < pl.n;) {
-        const bool pair = i + 1 < pl.n && oim_pair_supported(pl.h[i], pl.w[i], D, dtype, passes[i].axis, passes[i].m,
+        const bool pair = radius == 1 && i + 1 < pl.n && oim_pair_supported(pl.h[i], pl.w[i], D, dtype, passes[i].axis, passes[i].m,
                                                              passes[i + 1].axis, passes[i + 1].m, vec);
         steps[n_steps++] = Step{i, pair ? 2 : 1};
         i += pair ? 2 : 1;
@@ -247,7 +264,10 @@ luvc_status luvc_oim_merge(const void* x, const int32_t* sizes_in, int B, int H,
         maps[s] = pm;
         n_in[s] = pl.h[i] * pl.w[i];
         luvc_status rc;
-        if (steps[s].count == 2)
+        if (radius != 1)
+            rc = oim_wide_pass(cur_x, cur_s, B, pl.h[i], pl.w[i], D, dtype, passes[i].axis, passes[i].m, radius, vec,
+                               ox, os, pm, cur_k, ok, sc, (double*)(ws + L.gram), (int32_t*)(ws + L.srcdest), st);
+        else if (steps[s].count == 2)
             rc = oim_pair_pass(cur_x, cur_s, B, pl.h[i], pl.w[i], D, dtype, passes[i].axis, ox, os, pm, cur_k, ok, st);
         else if (oim_halve_supported(pl.h[i], pl.w[i], D, dtype, passes[i].axis, passes[i].m, vec))
             rc = oim_halve_pass(cur_x, cur_s, B, pl.h[i], pl.w[i], D, dtype, passes[i].axis, ox, os, pm, cur_k, ok, st);
@@ -261,6 +281,31 @@ luvc_status luvc_oim_merge(const void* x, const int32_t* sizes_in, int B, int H,
     }
     if (merged_map && n_steps > 1) return oim_compose(maps, n_in, n_steps, B, H * W, merged_map, st);
     return LUVC_OK;
+}
+
+luvc_status luvc_oim_merge(const void* x, const int32_t* sizes_in, int B, int H, int W, int D, luvc_dtype dtype,
+                           const luvc_oim_pass* passes, int n_passes, int64_t target_tokens,
+                           void* x_out, int32_t* sizes_out, int32_t* merged_map, int32_t* kept_map,
+                           void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    return oim_merge_impl(x, sizes_in, B, H, W, D, dtype, passes, n_passes, 1, target_tokens, x_out, sizes_out, merged_map, kept_map,
+                          workspace, workspace_bytes, hip_stream);
+}
+
+size_t luvc_oim_wide_workspace_bytes(int B, int H, int W, int D, luvc_dtype dtype, const luvc_oim_pass* passes, int n_passes, int radius)
+{
+    OimPlan pl;
+    if (!dtype_ok(dtype) || radius < 0 || !walk_schedule(B, H, W, D, passes, n_passes, &pl)) return 0;
+    return oim_layout(B, D, dtype, pl, passes, radius).bytes;
+}
+
+luvc_status luvc_oim_merge_wide(const void* x, const int32_t* sizes_in, int B, int H, int W, int D, luvc_dtype dtype,
+                                const luvc_oim_pass* passes, int n_passes, int radius, int64_t target_tokens,
+                                void* x_out, int32_t* sizes_out, int32_t* merged_map, int32_t* kept_map,
+                                void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    return oim_merge_impl(x, sizes_in, B, H, W, D, dtype, passes, n_passes, radius, target_tokens, x_out, sizes_out, merged_map, kept_map,
+                          workspace, workspace_bytes, hip_stream);
 }
 
 size_t luvc_spu_workspace_bytes(int B, int N, int D, luvc_dtype dtype, int sigma)

@@ -262,6 +262,21 @@ static luvc_status run_pass(const T* x, const int32_t* sizes_in, int B, int H, i
     return check_launch("oim pass");
 }
 
+luvc_status oim_norms(const void* x, int B, int H, int W, int D, luvc_dtype dt, int axis, bool vec,
+                      const OimScratch& ws, hipStream_t st)
+{
+    const int64_t n_tok = (int64_t)B * H * W;
+    const unsigned g1 = (unsigned)((n_tok * 64 + 255) / 256);
+    if (dt == LUVC_F32) {
+        if (vec) LUVC_LAUNCH("oim_pairdot", (oim_pairdot<float, true>), dim3(g1), dim3(256), 0, st, (const float*)x, ws.n2, ws.dn, n_tok, H, W, D, axis);
+        else     LUVC_LAUNCH("oim_pairdot", (oim_pairdot<float, false>), dim3(g1), dim3(256), 0, st, (const float*)x, ws.n2, ws.dn, n_tok, H, W, D, axis);
+    } else {
+        if (vec) LUVC_LAUNCH("oim_pairdot", (oim_pairdot<bf16_t, true>), dim3(g1), dim3(256), 0, st, (const bf16_t*)x, ws.n2, ws.dn, n_tok, H, W, D, axis);
+        else     LUVC_LAUNCH("oim_pairdot", (oim_pairdot<bf16_t, false>), dim3(g1), dim3(256), 0, st, (const bf16_t*)x, ws.n2, ws.dn, n_tok, H, W, D, axis);
+    }
+    return check_launch("oim norms");
+}
+
 luvc_status oim_general_pass(const void* x, const int32_t* sizes_in, int B, int H, int W, int D, luvc_dtype dt,
                              int axis, int m, bool vec, void* x_out, int32_t* sizes_out, int32_t* pass_map,
                              const int32_t* kept_prev, int32_t* kept_out,

@@ -20,6 +20,20 @@ luvc_status oim_general_pass(const void* x, const int32_t* sizes_in, int B, int 
                              const int32_t* kept_prev, int32_t* kept_out,
                              const OimScratch& ws, hipStream_t st);
 
+// Squared norms of all tokens into ws.n2 (ws.dn receives the dot products with the next token on the line).
+luvc_status oim_norms(const void* x, int B, int H, int W, int D, luvc_dtype dt, int axis, bool vec,
+                      const OimScratch& ws, hipStream_t st);
+
+// Pass with candidates beyond the adjacent destinations (oim_wide.hip): radius 0 = every destination of the
+// line, radius R >= 1 = destinations within 2R - 1 positions.  G and src_dest are scratch of the sizes below.
+constexpr int kMaxWideLineLen = 2048;
+size_t oim_wide_gram_bytes(int B, int H, int W, int axis);
+size_t oim_wide_srcdest_bytes(int B, int H, int W, int axis);
+luvc_status oim_wide_pass(const void* x, const int32_t* sizes_in, int B, int H, int W, int D, luvc_dtype dt,
+                          int axis, int m, int radius, bool vec, void* x_out, int32_t* sizes_out, int32_t* pass_map,
+                          const int32_t* kept_prev, int32_t* kept_out,
+                          const OimScratch& ws, double* G, int32_t* src_dest, hipStream_t st);
+
 // Fused pass for m = ceil(len/2) (oim_fast.hip); `vec` = rows are 16-byte aligned.
 bool oim_halve_supported(int H, int W, int D, luvc_dtype dt, int axis, int m, bool vec);
 luvc_status oim_halve_pass(const void* x, const int32_t* sizes_in, int B, int H, int W, int D, luvc_dtype dt, int axis,

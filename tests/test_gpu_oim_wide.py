@@ -1,0 +1,90 @@
+"""GPU parity: luvc_oim_merge_wide (candidates beyond the adjacent destinations, up to the whole line; the
+bipartite matching of the paper's Section 3.1 cost and its merge number 2) against the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2512_09010_amd import binding as lv
+from paper_2512_09010_amd import workloads as wl
+from gpu_util import OIM_MARGIN, RTOL, assert_close, round_mode, to_dev, to_host_f64
+
+pytestmark = pytest.mark.gpu
+W_AX, H_AX = 1, 0
+
+
+def run_wide(oracle, x_io, dtype, passes, radius, sizes=None, tag=""):
+    print(f"[oim wide] {tag} shape={x_io.shape} dtype={dtype} passes={passes} radius={radius}", flush=True)
+    ref = oracle.oim_merge(wl.widen(x_io, dtype), passes, sizes=sizes, R=radius, round_mode=round_mode(oracle, dtype))
+    s_dev = None if sizes is None else torch.from_numpy(np.ascontiguousarray(sizes, dtype=np.int32)).cuda()
+    out = lv.luvc_oim_merge_wide(to_dev(x_io, dtype), passes, radius, sizes=s_dev)
+    torch.cuda.synchronize()
+    assert out["x"].shape == ref["x"].shape
+    if not (ref["margin"] > OIM_MARGIN or ref["margin"] == 0.0):
+        pytest.skip(f"decision margin {ref['margin']:.3e} below {OIM_MARGIN}: maps not unique")
+    np.testing.assert_array_equal(out["sizes"].cpu().numpy().astype(np.int64), ref["sizes"])
+    np.testing.assert_array_equal(out["merged_map"].cpu().numpy(), ref["merged_map"])
+    np.testing.assert_array_equal(out["kept_map"].cpu().numpy(), ref["kept_map"])
+    got = to_host_f64(out["x"])
+    assert_close(got, ref["x"], RTOL[dtype], f"{tag} features")
+    if dtype == "bf16":
+        np.testing.assert_array_equal(got, ref["x"])         # fp64 merge in the oracle's term order, one rounding
+    return out, ref
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("radius", [0, 2, 3])
+@pytest.mark.parametrize("B,H,W,D,passes", [
+    (1, 1, 2, 8, [(W_AX, 1)]),
+    (1, 3, 1, 8, [(H_AX, 1)]),
+    (2, 5, 7, 24, [(W_AX, 4)]),
+    (2, 6, 9, 40, [(W_AX, 2), (H_AX, 2)]),                 # the paper's merge number 2
+    (1, 9, 6, 40, [(H_AX, 2), (W_AX, 2)]),                 # Algorithm 1 order: height first
+    (1, 16, 16, 72, [(W_AX, 2), (H_AX, 2), (W_AX, 2), (H_AX, 2), (W_AX, 2), (H_AX, 2)]),   # three OIM operations
+    (2, 4, 4, 33, [(W_AX, 1), (H_AX, 0)]),                 # rows that are not 16-byte multiples, m = 0 pass
+    (1, 3, 70, 48, [(W_AX, 35)]),                          # 35 sources x 35 destinations: several 16 x 16 tiles with ragged edges
+    (1, 71, 2, 16, [(H_AX, 10)]),
+    (2, 7, 11, 520, [(W_AX, 6), (H_AX, 4)]),               # channels not a multiple of the 32-channel block
+])
+def test_wide_small_random(oracle, dtype, radius, B, H, W, D, passes):
+    rng = np.random.default_rng(B * 1000 + H * 100 + W * 10 + D + radius)
+    x = wl.cast_io(rng.standard_normal((B, H, W, D)).astype(np.float32), dtype)
+    run_wide(oracle, x, dtype, passes, radius, tag="random")
+    sizes = rng.integers(1, 6, (B, H, W))
+    run_wide(oracle, x, dtype, passes, radius, sizes=sizes, tag="random+sizes")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_wide_many_sources_into_one_destination(oracle, dtype):
+    # every source of a line is a noisy copy of the line's last destination: they all fold into it
+    rng = np.random.default_rng(5)
+    B, H, W, D = 1, 4, 18, 64
+    x = rng.standard_normal((B, H, W, D)).astype(np.float32)
+    for h in range(H):
+        for w in range(0, W, 2):
+            x[0, h, w] = x[0, h, W - 1] + 0.01 * rng.standard_normal(D)
+    x = wl.cast_io(x, dtype)
+    out, ref = run_wide(oracle, x, dtype, [(W_AX, 9)], 0, tag="funnel")
+    assert (ref["sizes"][0, :, -1] == 10).all()              # nine sources and the destination itself
+    sizes = rng.integers(1, 4, (B, H, W))
+    run_wide(oracle, x, dtype, [(W_AX, 9)], 0, sizes=sizes, tag="funnel+sizes")
+
+
+def test_wide_radius_one_is_the_adjacent_matching(oracle):
+    rng = np.random.default_rng(9)
+    x = wl.cast_io(wl.smooth_field(rng, 2, 8, 10, 64, 2.0) + 0.1 * rng.standard_normal((2, 8, 10, 64)).astype(np.float32), "bf16")
+    passes = [(W_AX, 2), (H_AX, 2)]
+    a = lv.luvc_oim_merge_wide(to_dev(x, "bf16"), passes, 1)
+    b = lv.luvc_oim_merge(to_dev(x, "bf16"), passes)
+    torch.cuda.synchronize()
+    for k in ("x", "sizes", "merged_map", "kept_map"):
+        assert torch.equal(a[k], b[k]), k
+
+
+@pytest.mark.parametrize("i", [1, 3])
+def test_wide_workload_shapes(oracle, i):
+    """Encoder-sized grids of the benchmark workloads with the paper's setting: whole-line matching, merge number 2,
+    three OIM operations (W then H, three times)."""
+    w = wl.workload(i)
+    x = wl.oim_input(w)[:2]
+    passes = [(W_AX, 2), (H_AX, 2)] * 3
+    run_wide(oracle, x, w.dtype, passes, 0, tag=w.name)
