@@ -224,6 +224,10 @@ static luvc_status oim_merge_impl(const void* x, const int32_t* sizes_in, int B,
                 set_error("pass %d: wide matching supports lines of at most %d tokens", i, kMaxWideLineLen);
                 return LUVC_ERR_UNSUPPORTED;
             }
+    if (radius != 1 && (int64_t)H * W * D * (int64_t)esize(dtype) >= ((int64_t)1 << 31)) {
+        set_error("wide matching supports grids of less than 2 GiB per image");
+        return LUVC_ERR_UNSUPPORTED;
+    }
     const OimLayout L = oim_layout(B, D, dtype, pl, passes, radius);
     if (!workspace_ok(workspace, workspace_bytes, L.bytes)) return LUVC_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)hip_stream;

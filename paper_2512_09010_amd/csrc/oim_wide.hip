@@ -4,11 +4,11 @@
 // O(n_v^1.5 k) (Section 3.1) and the one its appendix runs with a merge number of 2; a destination can
 // absorb several sources.
 //
-// One pass = four launches:
-//   oim_pairdot    (oim.hip) squared norms of all tokens, fp64;
+// One pass = three launches:
 //   oim_line_gram  the source x destination dot products of every line, fp64, as a dense contraction
 //                  over the channels on the matrix cores (v_mfma_f64_16x16x4_f64): a wavefront owns a
-//                  16 x 16 tile of one line's matrix and walks the channels 32 at a time;
+//                  16 x 16 tile of one line's matrix and walks the channels 32 at a time; the squared
+//                  norms of the tokens fall out on the way;
 //   oim_decide_wide one workgroup per line: cosines, best destination per source (tie -> lower
 //                  position), the m best sources (tie -> lower position), survivor layout, maps;
 //   oim_merge_wide one wavefront per surviving token: copy, or size-weighted mean of the destination
@@ -25,38 +25,57 @@ namespace {
 typedef double f64x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((__vector_size__(16)));
 
-// 8 consecutive elements of a token as fp64; zeros past the end of the token (or for a token that is not there)
+// 8 consecutive elements of a token: fetched as raw words (so that several fetches can be in flight before the
+// first is used), widened to fp64 afterwards; zeros past the end of the token or for a token that is not there
 template <typename T, bool VECTOR> struct chan8;
 template <bool VECTOR> struct chan8<bf16_t, VECTOR> {
-    __device__ static __forceinline__ void load(const bf16_t* tok, int D, int d0, bool present, double (&o)[8])
+    struct raw_t { u32x4 q; };
+    // r spans the whole image (one descriptor for the wavefront); tok_off = byte offset of the token in it
+    __device__ static __forceinline__ raw_t fetch(__amdgpu_buffer_rsrc_t r, uint32_t tok_off, const bf16_t* tok, int D, int d0, bool present)
     {
-        if (VECTOR) {
-            const __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(tok), 0, present ? D * 2 : 0, 0x00020000);
-            const u32x4 q = __builtin_amdgcn_raw_buffer_load_b128(r, d0 * 2, 0, 0);
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                o[2 * i] = (double)__uint_as_float(q[i] << 16);
-                o[2 * i + 1] = (double)__uint_as_float(q[i] & 0xffff0000u);
-            }
+        raw_t o;
+        if (VECTOR) {        // rows are multiples of 16 bytes: a piece lies inside the token or past its end, never across
+            o.q = __builtin_amdgcn_raw_buffer_load_b128(r, (present && d0 < D) ? tok_off + (uint32_t)d0 * 2u : 0x80000000u, 0, 0);
         } else {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) o[i] = (present && d0 + i < D) ? (double)bf16_to_f32(tok[d0 + i].bits) : 0.0;
+            for (int i = 0; i < 4; ++i) {
+                const uint32_t lo = (present && d0 + 2 * i < D) ? tok[d0 + 2 * i].bits : 0u;
+                const uint32_t hi = (present && d0 + 2 * i + 1 < D) ? tok[d0 + 2 * i + 1].bits : 0u;
+                o.q[i] = lo | (hi << 16);
+            }
+        }
+        return o;
+    }
+    __device__ static __forceinline__ void widen(const raw_t& w, double (&o)[8])
+    {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            o[2 * i] = (double)__uint_as_float(w.q[i] << 16);
+            o[2 * i + 1] = (double)__uint_as_float(w.q[i] & 0xffff0000u);
         }
     }
 };
 template <bool VECTOR> struct chan8<float, VECTOR> {
-    __device__ static __forceinline__ void load(const float* tok, int D, int d0, bool present, double (&o)[8])
+    struct raw_t { u32x4 q0, q1; };
+    __device__ static __forceinline__ raw_t fetch(__amdgpu_buffer_rsrc_t r, uint32_t tok_off, const float* tok, int D, int d0, bool present)
     {
+        raw_t o;
         if (VECTOR) {
-            const __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(tok), 0, present ? D * 4 : 0, 0x00020000);
-            const u32x4 q0 = __builtin_amdgcn_raw_buffer_load_b128(r, d0 * 4, 0, 0);
-            const u32x4 q1 = __builtin_amdgcn_raw_buffer_load_b128(r, d0 * 4 + 16, 0, 0);
-#pragma unroll
-            for (int i = 0; i < 4; ++i) { o[i] = (double)__uint_as_float(q0[i]); o[4 + i] = (double)__uint_as_float(q1[i]); }
+            o.q0 = __builtin_amdgcn_raw_buffer_load_b128(r, (present && d0 < D) ? tok_off + (uint32_t)d0 * 4u : 0x80000000u, 0, 0);
+            o.q1 = __builtin_amdgcn_raw_buffer_load_b128(r, (present && d0 + 4 < D) ? tok_off + (uint32_t)d0 * 4u + 16u : 0x80000000u, 0, 0);
         } else {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) o[i] = (present && d0 + i < D) ? (double)tok[d0 + i] : 0.0;
+            for (int i = 0; i < 4; ++i) {
+                o.q0[i] = (present && d0 + i < D) ? __float_as_uint(tok[d0 + i]) : 0u;
+                o.q1[i] = (present && d0 + 4 + i < D) ? __float_as_uint(tok[d0 + 4 + i]) : 0u;
+            }
         }
+        return o;
+    }
+    __device__ static __forceinline__ void widen(const raw_t& w, double (&o)[8])
+    {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { o[i] = (double)__uint_as_float(w.q0[i]); o[4 + i] = (double)__uint_as_float(w.q1[i]); }
     }
 };
 
@@ -66,40 +85,70 @@ template <bool VECTOR> struct chan8<float, VECTOR> {
 // Lane l of a wavefront feeds source i = l % 16 and destination i of its tile, channels 8 (l / 16) .. + 7 of
 // every block of 32: matrix instruction e of a block contracts channels {e, 8 + e, 16 + e, 24 + e}.
 // Result layout of the instruction: lane l, register r holds row 4 r + l / 16 (source), column l % 16.
+// The squared norms fall out on the way (every lane sees all channels of its two tokens, a quarter each):
+// the tiles of the first column of a line write those of the sources, the first row those of the destinations.
+constexpr int kGramSteps = 4;                    // 32-channel blocks fetched before the first is used
 template <typename T, bool VECTOR>
 __global__ void __launch_bounds__(256)
-oim_line_gram(const T* __restrict__ x, double* __restrict__ G /* [B*nlines, n_src, n_dst] */,
+oim_line_gram(const T* __restrict__ x, double* __restrict__ G /* [B*nlines, n_src, n_dst] */, double* __restrict__ n2 /* [B,H*W] */,
               int H, int W, int D, int axis, int64_t n_tiles, int tiles_s, int tiles_d)
 {
+    using ch = chan8<T, VECTOR>;
     const int lane = threadIdx.x & 63;
-    const int64_t tile = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (tile >= n_tiles) return;
+    const uint32_t tile = __builtin_amdgcn_readfirstlane(blockIdx.x * 4u + (threadIdx.x >> 6));   // fewer than 2^31 tiles (host check)
+    if (tile >= (uint32_t)n_tiles) return;
     const int len = axis ? W : H, nlines = axis ? H : W;
     const int n_src = (len + 1) / 2, n_dst = len / 2;
-    const int td = (int)(tile % tiles_d), ts = (int)((tile / tiles_d) % tiles_s);
-    const int64_t bl = tile / ((int64_t)tiles_d * tiles_s);             // b * nlines + line
-    const int line = (int)(bl % nlines);
-    const int64_t b = bl / nlines;
+    const int td = (int)(tile % (uint32_t)tiles_d), ts = (int)((tile / (uint32_t)tiles_d) % (uint32_t)tiles_s);
+    const int64_t bl = tile / ((uint32_t)tiles_d * (uint32_t)tiles_s);  // b * nlines + line
+    const int line = (int)((uint32_t)bl % (uint32_t)nlines);
+    const int64_t b = (uint32_t)bl / (uint32_t)nlines;
     const int i = lane & 15, g = lane >> 4;
     const int js = ts * 16 + i, jd = td * 16 + i;                         // source / destination index on the line
     const bool has_s = js < n_src, has_d = jd < n_dst;
     const int ps = 2 * js, pd = 2 * jd + 1;                               // their positions
     auto flat = [&](int p) -> int64_t { return axis ? (int64_t)line * W + p : (int64_t)p * W + line; };
-    const T* tok_s = x + (b * H * W + (has_s ? flat(ps) : 0)) * D;
-    const T* tok_d = x + (b * H * W + (has_d ? flat(pd) : 0)) * D;
+    const int64_t t_s = b * H * W + (has_s ? flat(ps) : 0), t_d = b * H * W + (has_d ? flat(pd) : 0);
+    const T* tok_s = x + t_s * D;
+    const T* tok_d = x + t_d * D;
+    // one descriptor over the image for the whole wavefront (a descriptor per token would have to be walked lane by lane)
+    const __amdgpu_buffer_rsrc_t rimg = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<T*>(x) + b * H * W * D, 0, (int)((int64_t)H * W * D * (int64_t)sizeof(T)), 0x00020000);
+    const uint32_t off_s = (uint32_t)((has_s ? flat(ps) : 0) * D * (int64_t)sizeof(T));
+    const uint32_t off_d = (uint32_t)((has_d ? flat(pd) : 0) * D * (int64_t)sizeof(T));
     f64x4 acc = {0.0, 0.0, 0.0, 0.0};
-    for (int d0 = 0; d0 < D; d0 += 32) {
-        double a[8], c[8];
-        chan8<T, VECTOR>::load(tok_s, D, d0 + 8 * g, has_s, a);
-        chan8<T, VECTOR>::load(tok_d, D, d0 + 8 * g, has_d, c);
+    double na = 0.0, nc = 0.0;
+    for (int d0 = 0; d0 < D; d0 += 32 * kGramSteps) {
+        typename ch::raw_t ra[kGramSteps], rc[kGramSteps];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) acc = __builtin_amdgcn_mfma_f64_16x16x4f64(a[e], c[e], acc, 0, 0, 0);
+        for (int u = 0; u < kGramSteps; ++u) {                            // past the end of the token: zeros
+            ra[u] = ch::fetch(rimg, off_s, tok_s, D, d0 + 32 * u + 8 * g, has_s);
+            rc[u] = ch::fetch(rimg, off_d, tok_d, D, d0 + 32 * u + 8 * g, has_d);
+        }
+#pragma unroll
+        for (int u = 0; u < kGramSteps; ++u) {
+            double a[8], c[8];
+            ch::widen(ra[u], a);
+            ch::widen(rc[u], c);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                acc = __builtin_amdgcn_mfma_f64_16x16x4f64(a[e], c[e], acc, 0, 0, 0);
+                na = fma(a[e], a[e], na);
+                nc = fma(c[e], c[e], nc);
+            }
+        }
     }
     double* Gl = G + bl * n_src * n_dst;
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
         const int row = ts * 16 + 4 * r + g, col = td * 16 + i;
         if (row < n_src && col < n_dst) Gl[(int64_t)row * n_dst + col] = acc[r];
+    }
+    na += __shfl_xor(na, 16, kWave); na += __shfl_xor(na, 32, kWave);     // the four channel quarters of token i
+    nc += __shfl_xor(nc, 16, kWave); nc += __shfl_xor(nc, 32, kWave);
+    if (g == 0) {
+        if (td == 0 && has_s) n2[t_s] = na;
+        if (ts == 0 && has_d) n2[t_d] = nc;
     }
 }
 
@@ -131,24 +180,34 @@ oim_decide_wide(const double* __restrict__ n2, const double* __restrict__ G,
     const double* Gl = G + (int64_t)blockIdx.x * n_src * n_dst;
 
     for (int p = tid; p < len; p += blockDim.x) {
-        const double v = sqrt(n2[img + in_flat(p)]);
+        const double v = n_dst > 0 ? sqrt(n2[img + in_flat(p)]) : 1.0;   // a line of one token has no norms (and no decisions)
         nrm[p] = v < 1e-12 ? 1e-12 : v;
         merged[p] = 0;
     }
     __syncthreads();
-    for (int j = tid; j < n_src; j += blockDim.x) {
-        const int a = 2 * j;
-        double bs = -INFINITY;
-        int bc = -1;
-        for (int k = 0; k < n_dst; ++k) {                       // ascending position: a tie keeps the lower one
-            const int c = 2 * k + 1;
-            const int dist = c > a ? c - a : a - c;
-            if (radius > 0 && dist > 2 * radius - 1) continue;
-            const double s = Gl[(int64_t)j * n_dst + k] / (nrm[a] * nrm[c]);
-            if (bc < 0 || s > bs) { bs = s; bc = c; }
+    // one wavefront per source, lanes over the destinations; a lane walks its candidates in ascending position,
+    // the lanes are then combined with the same rule: higher cosine wins, equal cosines keep the lower position
+    {
+        const int lane = tid & 63, wv = tid >> 6, nwv = blockDim.x >> 6;
+        for (int j = wv; j < n_src; j += nwv) {
+            const int a = 2 * j;
+            double bs = -INFINITY;
+            int bc = -1;
+            for (int k = lane; k < n_dst; k += 64) {
+                const int c = 2 * k + 1;
+                const int dist = c > a ? c - a : a - c;
+                if (radius > 0 && dist > 2 * radius - 1) continue;
+                const double s = Gl[(int64_t)j * n_dst + k] / (nrm[a] * nrm[c]);
+                if (bc < 0 || s > bs) { bs = s; bc = c; }
+            }
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) {
+                const double os = __shfl_xor(bs, o, kWave);
+                const int oc = __shfl_xor(bc, o, kWave);
+                if (oc >= 0 && (bc < 0 || os > bs || (os == bs && oc < bc))) { bs = os; bc = oc; }
+            }
+            if (lane == 0) { best[j] = bc; score[j] = bs; }
         }
-        best[j] = bc;
-        score[j] = bs;
     }
     __syncthreads();
     if (m == n_src) {
@@ -319,14 +378,13 @@ static luvc_status run_wide(const T* x, const int32_t* sizes_in, int B, int H, i
     const int len = axis ? W : H, nlines = axis ? H : W, n_src = (len + 1) / 2, n_dst = len / 2;
     const int Ho = axis ? H : H - m, Wo = axis ? W - m : W;
     const int64_t n_out = (int64_t)B * Ho * Wo;
-    luvc_status rc = oim_norms((const void*)x, B, H, W, D, std::is_same<T, float>::value ? LUVC_F32 : LUVC_BF16, axis, vec, ws, st);
-    if (rc != LUVC_OK) return rc;
     if (n_dst > 0) {
         const int tiles_s = (n_src + 15) / 16, tiles_d = (n_dst + 15) / 16;
         const int64_t n_tiles = (int64_t)B * nlines * tiles_s * tiles_d;
+        if (n_tiles >= ((int64_t)1 << 31)) { set_error("wide matching: too many 16 x 16 tiles in one pass"); return LUVC_ERR_UNSUPPORTED; }
         const unsigned g1 = (unsigned)((n_tiles + 3) / 4);
-        if (vec) LUVC_LAUNCH("oim_line_gram", (oim_line_gram<T, true>), dim3(g1), dim3(256), 0, st, x, G, H, W, D, axis, n_tiles, tiles_s, tiles_d);
-        else     LUVC_LAUNCH("oim_line_gram", (oim_line_gram<T, false>), dim3(g1), dim3(256), 0, st, x, G, H, W, D, axis, n_tiles, tiles_s, tiles_d);
+        if (vec) LUVC_LAUNCH("oim_line_gram", (oim_line_gram<T, true>), dim3(g1), dim3(256), 0, st, x, G, ws.n2, H, W, D, axis, n_tiles, tiles_s, tiles_d);
+        else     LUVC_LAUNCH("oim_line_gram", (oim_line_gram<T, false>), dim3(g1), dim3(256), 0, st, x, G, ws.n2, H, W, D, axis, n_tiles, tiles_s, tiles_d);
     }
     const size_t lds = sizeof(double) * (size_t)(n_src + len) + sizeof(int) * (size_t)(n_src + len + 256 + 1) + (size_t)len + 16;
     LUVC_LAUNCH("oim_decide_wide", oim_decide_wide, dim3((unsigned)(B * nlines)), dim3(256), lds, st, ws.n2, G, H, W, axis, m, radius,
