@@ -30,6 +30,8 @@ def parse():
     ap.add_argument("--config", type=int, default=1, help="workload 0..4 of BASELINE.json (default 1: the metric's config)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--no-pipelined", dest="pipelined", action="store_false", help="skip the two-stream leg")
+    ap.add_argument("--oim-wide", action="store_true",
+                    help="also time luvc_oim_merge_wide on the workload's grid in the paper's setting (whole-line matching, merge number 2, three operations)")
     ap.add_argument("--rotate-mb", type=float, default=600.0, help="distinct input bytes cycled through (defeats cache reuse)")
     return ap.parse_args()
 
@@ -241,10 +243,62 @@ def main():
     }
     if pipelined:
         result["pipelined"] = pipelined
+    if args.oim_wide:
+        result["oim_wide"] = oim_wide_leg(lv, torch, w, xs_oim, n_rot, tdt, code, es, stream, args.steps)
 
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, x_oim_host, x_spu_host)
     print(json.dumps(result))
+
+
+def oim_wide_leg(lv, torch, w, xs_oim, n_rot, tdt, code, es, stream, steps):
+    """luvc_oim_merge_wide in the paper's appendix setting on the workload's encoder grid: every source of a line is
+    compared with every destination of the line, merge number 2, three OIM operations (W then H, three times)."""
+    import numpy as np
+    dev = xs_oim[0].device
+    passes = [(1, 2), (0, 2)] * 3
+    Ho, Wo = lv.out_grid(w.H, w.W, passes)
+    out = dict(x=torch.empty((w.grids, Ho, Wo, w.D), dtype=tdt, device=dev), sizes=torch.empty((w.grids, Ho, Wo), dtype=torch.int32, device=dev),
+               merged_map=torch.empty((w.grids, w.H * w.W), dtype=torch.int32, device=dev),
+               kept_map=torch.empty((w.grids, Ho * Wo), dtype=torch.int32, device=dev))
+    ws = torch.empty(lv.luvc_oim_wide_workspace_bytes(w.grids, w.H, w.W, w.D, code, passes, 0), dtype=torch.uint8, device=dev)
+
+    def call(i):
+        lv.luvc_oim_merge_wide(xs_oim[i % n_rot], passes, 0, workspace=ws, stream=stream, out=out)
+
+    for i in range(5):
+        call(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        call(i)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    n_prof = min(steps, 20)
+    prof = lv.LaunchProfile(n_prof * 32)
+    prof.start()
+    for i in range(n_prof):
+        call(i)
+    prof.stop()
+    torch.cuda.synchronize()
+    per = {}
+    for name, t in prof.results():
+        per.setdefault(name, []).append(t)
+    prof.close()
+    # algorithmic work: the source x destination contraction of every line of every pass (2 flops per product);
+    # the merge reads every token once and writes the survivors
+    flops, H, W = 0.0, w.H, w.W
+    for axis, m in passes:
+        ln, nl = (W, H) if axis else (H, W)
+        flops += 2.0 * w.grids * nl * ((ln + 1) // 2) * (ln // 2) * w.D
+        H, W = (H, W - m) if axis else (H - m, W)
+    g = float(np.sum(per.get("oim_line_gram", [0.0]))) / n_prof
+    kernels = {k: {"launches_per_call": len(v) / n_prof, "avg_us": round(float(np.mean(v)) * 1e3, 2)} for k, v in per.items()}
+    return {"what": "whole-line matching (radius 0), m = 2, passes (W,2),(H,2) x 3", "ms_per_call": round(ms, 5),
+            "tokens_per_s": round(w.tokens_in / (ms * 1e-3), 1), "kernels": kernels,
+            "roofline": {"kernel": "oim_line_gram", "bound": "mfma", "dtype": "f64", "achieved": round(flops / (g * 1e-3) / 1e12, 2) if g else None,
+                         "peak": 78.6, "unit": "TFLOP/s", "frac": round(flops / (g * 1e-3) / 1e12 / 78.6, 4) if g else None,
+                         "algorithmic_flops_per_call": int(flops)}}
 
 
 def cpu_baseline(w, x_oim_host, x_spu_host):

@@ -135,3 +135,22 @@ def test_spu_rejects_bad_arguments(L):
     assert L.luvc_spu_prune(*pr(k=65)) == lv.LUVC_ERR_INVALID_ARG
     assert L.luvc_spu_prune(*pr(rs=4)) == lv.LUVC_ERR_INVALID_ARG
     assert L.luvc_spu_prune(*pr(B=-3)) == lv.LUVC_ERR_INVALID_ARG
+
+
+def test_wide_matching_arguments(L):
+    """luvc_oim_merge_wide / luvc_oim_wide_workspace_bytes validate on the host: nothing is enqueued for a bad call."""
+    passes = [(1, 2), (0, 2)]
+    need1 = lv.luvc_oim_wide_workspace_bytes(2, 16, 16, 64, lv.LUVC_BF16, passes, 1)
+    need0 = lv.luvc_oim_wide_workspace_bytes(2, 16, 16, 64, lv.LUVC_BF16, passes, 0)
+    assert need1 == lv.luvc_oim_workspace_bytes(2, 16, 16, 64, lv.LUVC_BF16, passes)     # radius 1 is the adjacent matching
+    assert need0 >= need1 + 2 * 16 * 8 * 8 * 8 and need0 % 256 == 0                      # + the source x destination matrices
+    assert lv.luvc_oim_wide_workspace_bytes(2, 16, 16, 64, lv.LUVC_BF16, passes, -1) == 0
+    parr = lv._passes(passes)
+    rc = L.luvc_oim_merge_wide(None, None, 2, 16, 16, 64, lv.LUVC_BF16, parr, 2, 0, 0, None, None, None, None, None, 0, None)
+    assert rc == lv.LUVC_ERR_INVALID_ARG
+    rc = L.luvc_oim_merge_wide(ctypes.c_void_p(256), None, 2, 16, 16, 64, lv.LUVC_BF16, parr, 2, -3, 0,
+                               ctypes.c_void_p(256), ctypes.c_void_p(256), None, None, ctypes.c_void_p(256), 1 << 30, None)
+    assert rc == lv.LUVC_ERR_INVALID_ARG and b"radius" in L.luvc_last_error()
+    rc = L.luvc_oim_merge_wide(ctypes.c_void_p(256), None, 1, 1, 4096, 64, lv.LUVC_BF16, lv._passes([(1, 2)]), 1, 0, 0,
+                               ctypes.c_void_p(256), ctypes.c_void_p(256), None, None, ctypes.c_void_p(256), 1 << 40, None)
+    assert rc == lv.LUVC_ERR_UNSUPPORTED                                                  # line longer than the wide path takes
