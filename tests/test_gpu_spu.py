@@ -84,6 +84,32 @@ def test_score_repeated_calls_with_poisoned_workspace(oracle):
         assert bad.item() == 0, (B, N, D, sigma, bad.item())
 
 
+def test_score_calls_overlapping_on_two_streams():
+    """Score calls in flight at the same time on two streams (own workspaces) share nothing but the library's
+    static completion counters, which are handed out per call: every result must equal the serial one bit for bit."""
+    rng = np.random.default_rng(123)
+    cases = [(4, 1024, 3584 // 4, 102), (3, 720, 512, 54), (2, 196, 300, 4)]          # fft (Q = 16, 15) and the one-launch dense path
+    data = []
+    for B, N, D, sigma in cases:
+        x = to_dev(wl.cast_io(rng.standard_normal((B, N, D)).astype(np.float32), "bf16"), "bf16")
+        want = lv.luvc_spu_score(x, sigma, True)
+        ws = [torch.empty(lv.luvc_spu_workspace_bytes(B, N, D, lv.LUVC_BF16, sigma), dtype=torch.uint8, device="cuda") for _ in range(2)]
+        outs = [torch.empty((B, N), dtype=torch.float32, device="cuda") for _ in range(2)]
+        data.append((x, sigma, want, ws, outs))
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    bad = [torch.zeros((), dtype=torch.int64, device="cuda") for _ in range(2)]
+    for it in range(30):
+        for k, st in enumerate(streams):
+            x, sigma, want, ws, outs = data[(it + k) % len(data)]
+            with torch.cuda.stream(st):
+                outs[k].fill_(float("nan"))
+                lv.luvc_spu_score(x, sigma, True, workspace=ws[k], stream=st, out=outs[k])
+                bad[k] += (outs[k].view(torch.int32) != want.view(torch.int32)).sum()
+    torch.cuda.synchronize()
+    assert bad[0].item() == 0 and bad[1].item() == 0, (bad[0].item(), bad[1].item())
+
+
 def test_score_special_signals(oracle):
     N, D = 64, 64
     n = np.arange(N)
