@@ -47,6 +47,12 @@ def lib() -> ctypes.CDLL:
         L.oracle_oim_pass.restype = i
         L.oracle_oim_merge.argtypes = [c_dp, c_lp, i, i, i, i, c_ip, c_ip, i, i, i, c_dp, c_lp, c_ip, c_ip, c_dp]
         L.oracle_oim_merge.restype = i
+        L.oracle_oim_apply.argtypes = [c_dp, c_lp, i, i, i, i, i, c_ip, c_ip, i, c_dp]
+        L.oracle_oim_apply.restype = i
+        L.oracle_oim_merge_keyed.argtypes = [c_dp, c_dp, c_lp, i, i, i, i, i, c_ip, c_ip, i, i, i, c_dp, c_dp, c_lp, c_ip, c_ip, c_dp]
+        L.oracle_oim_merge_keyed.restype = i
+        L.oracle_value_enhance.argtypes = [c_dp, c_lp, ctypes.c_int64, i, i, c_dp]
+        L.oracle_value_enhance.restype = i
         L.oracle_spu_mask.argtypes = [i, i, i, i]
         L.oracle_spu_mask.restype = ctypes.c_double
         L.oracle_spu_score.argtypes = [c_dp, i, i, i, i, i, c_dp, c_dp, c_dp]
@@ -107,6 +113,46 @@ def oim_merge(x, passes, sizes=None, R=1, round_mode=ROUND_NONE):
     if rc != 0:
         raise ValueError("oracle_oim_merge rejected its arguments")
     return dict(x=x_out, sizes=s_out, merged_map=merged, kept_map=kept, margin=margin.value)
+
+
+def oim_merge_keyed(x, metric, passes, sizes=None, R=1, round_mode=ROUND_NONE):
+    """Decisions on metric [B,H,W,Dm], merge applied to x [B,H,W,D] (and to the metric).
+
+    Returns dict(x, metric, sizes, merged_map, kept_map, margin).
+    """
+    x, metric = _f64(x), _f64(metric)
+    B, H, W, D = x.shape
+    Dm = metric.shape[3]
+    assert metric.shape[:3] == (B, H, W)
+    Ho, Wo = out_shape(H, W, passes)
+    if Ho < 1 or Wo < 1:
+        raise ValueError("schedule removes every token of an axis")
+    s_in = None if sizes is None else np.ascontiguousarray(sizes, dtype=np.int64).reshape(B, H, W)
+    x_out = np.empty((B, Ho, Wo, D), np.float64)
+    k_out = np.empty((B, Ho, Wo, Dm), np.float64)
+    s_out = np.empty((B, Ho, Wo), np.int64)
+    merged = np.empty((B, H * W), np.int32)
+    kept = np.empty((B, Ho * Wo), np.int32)
+    axes = np.array([p[0] for p in passes], np.int32)
+    ms = np.array([p[1] for p in passes], np.int32)
+    margin = ctypes.c_double(float("inf"))
+    rc = lib().oracle_oim_merge_keyed(_dp(x), _dp(metric), _lp(s_in), B, H, W, D, Dm, _ip(axes), _ip(ms), len(passes), R, round_mode,
+                                      _dp(x_out), _dp(k_out), _lp(s_out), _ip(merged), _ip(kept), ctypes.byref(margin))
+    if rc != 0:
+        raise ValueError("oracle_oim_merge_keyed rejected its arguments")
+    return dict(x=x_out, metric=k_out, sizes=s_out, merged_map=merged, kept_map=kept, margin=margin.value)
+
+
+def value_enhance(v, sizes, round_mode=ROUND_NONE):
+    """v [..., D] + log(sizes [...]) on every channel (Eq. 3)."""
+    v = _f64(v)
+    s = np.ascontiguousarray(sizes, dtype=np.int64)
+    assert s.shape == v.shape[:-1]
+    out = np.empty_like(v)
+    rc = lib().oracle_value_enhance(_dp(v), _lp(s), int(s.size), v.shape[-1], round_mode, _dp(out))
+    if rc != 0:
+        raise ValueError("oracle_value_enhance rejected its arguments")
+    return out
 
 
 def spu_mask(N, sigma, use_hamming=True):

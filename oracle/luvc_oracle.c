@@ -33,6 +33,11 @@
  *     pass-band f(k) <= sigma (two sided so that the filtered signal is real);
  *   - kept indices are returned in ascending order, ties -> lower index.
  *
+ *   - Section 3.1 counts the similarity cost in "the dimension of keys": the
+ *     keyed call takes its decisions on a separate metric tensor and applies
+ *     the merge to the tokens (oracle_oim_merge_keyed); Eq. 3's value
+ *     enhancement V + log(s) is oracle_value_enhance.
+ *
  * Pinned by tests/test_oracle_*.py (brute-force matcher, hand cases, mass
  * conservation, numpy.fft, constant / low-band signals, Parseval, stable sort).
  * Unpinned parameters (not functions): the cut-off sigma and the cascade keep
@@ -274,6 +279,134 @@ int oracle_oim_merge(const double *x, const int64_t *sizes_in,
     }
     free(cur); free(cur_s); free(tot_merged); free(tot_kept);
     return rc;
+}
+
+/* ------------------------------------------------ OIM with a separate metric */
+
+/*
+ * The merge of one pass applied to a second tensor: the groups are those of
+ * `merged_map` / `kept_map` of a pass that was decided on another tensor
+ * (Section 3.1 counts the similarity cost in k, "the dimension of keys": the
+ * similarity is taken on the keys, the merge is applied to the tokens).
+ * Each output slot q receives the size-weighted mean of its group: the
+ * anchor kept_map[q] first, then the other members in ascending flat index
+ * (= ascending position on the line), exactly the order of oracle_oim_pass.
+ *   y        [B,H,W,Dy];  y_out [B,Ho*Wo,Dy]
+ */
+int oracle_oim_apply(const double *y, const int64_t *sizes_in, int B, int H, int W, int Dy,
+                     int n_out, const int32_t *merged_map, const int32_t *kept_map,
+                     int round_mode, double *y_out)
+{
+    if (B < 0 || H < 1 || W < 1 || Dy < 1 || n_out < 1) return -1;
+    const int64_t n_in = (int64_t)H * W;
+    double *acc = (double *)malloc(sizeof(double) * (size_t)Dy);
+    for (int b = 0; b < B; ++b) {
+        for (int q = 0; q < n_out; ++q) {
+            const int64_t p = kept_map[(int64_t)b * n_out + q];
+            const int64_t s_p = sizes_in ? sizes_in[b * n_in + p] : 1;
+            int64_t S = s_p;
+            for (int d = 0; d < Dy; ++d) acc[d] = (double)s_p * y[(b * n_in + p) * Dy + d];
+            for (int64_t a = 0; a < n_in; ++a) {
+                if (a == p || merged_map[b * n_in + a] != q) continue;
+                const int64_t s_a = sizes_in ? sizes_in[b * n_in + a] : 1;
+                S += s_a;
+                for (int d = 0; d < Dy; ++d) acc[d] += (double)s_a * y[(b * n_in + a) * Dy + d];
+            }
+            double *o = y_out + ((int64_t)b * n_out + q) * Dy;
+            if (S == s_p)
+                for (int d = 0; d < Dy; ++d) o[d] = round_to_io(y[(b * n_in + p) * Dy + d], round_mode);
+            else
+                for (int d = 0; d < Dy; ++d) o[d] = round_to_io(acc[d] / (double)S, round_mode);
+        }
+    }
+    free(acc);
+    return 0;
+}
+
+/*
+ * A whole OIM call whose decisions are taken on `metric` [B,H,W,Dm] (the
+ * keys) while `x` [B,H,W,D] follows: every pass is decided by
+ * oracle_oim_pass on the current metric, its merge is applied to x with
+ * oracle_oim_apply, both tensors are rounded to the I/O type after every
+ * pass, maps are composed as in oracle_oim_merge.  metric_out may be NULL.
+ */
+int oracle_oim_merge_keyed(const double *x, const double *metric, const int64_t *sizes_in,
+                           int B, int H, int W, int D, int Dm,
+                           const int32_t *pass_axis, const int32_t *pass_m, int n_passes,
+                           int R, int round_mode,
+                           double *x_out, double *metric_out, int64_t *sizes_out,
+                           int32_t *merged_map, int32_t *kept_map, double *margin)
+{
+    if (n_passes < 0) return -1;
+    const int64_t n_in = (int64_t)H * W;
+    int h = H, w = W;
+    double *cx = (double *)malloc(sizeof(double) * (size_t)(B * n_in * D + 1));
+    double *ck = (double *)malloc(sizeof(double) * (size_t)(B * n_in * Dm + 1));
+    int64_t *cs = (int64_t *)malloc(sizeof(int64_t) * (size_t)(B * n_in + 1));
+    int32_t *tot_merged = (int32_t *)malloc(sizeof(int32_t) * (size_t)(B * n_in + 1));
+    int32_t *tot_kept = (int32_t *)malloc(sizeof(int32_t) * (size_t)(B * n_in + 1));
+    memcpy(cx, x, sizeof(double) * (size_t)(B * n_in * D));
+    memcpy(ck, metric, sizeof(double) * (size_t)(B * n_in * Dm));
+    for (int64_t i = 0; i < B * n_in; ++i) cs[i] = sizes_in ? sizes_in[i] : 1;
+    for (int b = 0; b < B; ++b)
+        for (int64_t p = 0; p < n_in; ++p) tot_merged[b * n_in + p] = tot_kept[b * n_in + p] = (int32_t)p;
+    int rc = 0;
+    for (int i = 0; i < n_passes && rc == 0; ++i) {
+        const int axis = pass_axis[i], m = pass_m[i];
+        const int ho = axis ? h : h - m, wo = axis ? w - m : w;
+        if ((axis != 0 && axis != 1) || ho < 1 || wo < 1) { rc = -1; break; }
+        const int64_t n_cur = (int64_t)h * w, n_new = (int64_t)ho * wo;
+        double *nk_ = (double *)malloc(sizeof(double) * (size_t)(B * n_new * Dm + 1));
+        double *nx = (double *)malloc(sizeof(double) * (size_t)(B * n_new * D + 1));
+        int64_t *ns = (int64_t *)malloc(sizeof(int64_t) * (size_t)(B * n_new + 1));
+        int32_t *mm = (int32_t *)malloc(sizeof(int32_t) * (size_t)(B * n_cur + 1));
+        int32_t *km = (int32_t *)malloc(sizeof(int32_t) * (size_t)(B * n_new + 1));
+        rc = oracle_oim_pass(ck, cs, B, h, w, Dm, axis, m, R, round_mode, nk_, ns, mm, km, margin);
+        if (rc == 0) rc = oracle_oim_apply(cx, cs, B, h, w, D, (int)n_new, mm, km, round_mode, nx);
+        if (rc == 0) {
+            for (int b = 0; b < B; ++b)
+                for (int64_t p = 0; p < n_in; ++p)
+                    tot_merged[b * n_in + p] = mm[b * n_cur + tot_merged[b * n_in + p]];
+            int32_t *nk = (int32_t *)malloc(sizeof(int32_t) * (size_t)(B * n_in + 1));
+            for (int b = 0; b < B; ++b)
+                for (int64_t q = 0; q < n_new; ++q)
+                    nk[b * n_in + q] = tot_kept[b * n_in + km[b * n_new + q]];
+            free(tot_kept);
+            tot_kept = nk;
+        }
+        free(cx); free(ck); free(cs); free(mm); free(km);
+        cx = nx; ck = nk_; cs = ns; h = ho; w = wo;
+    }
+    if (rc == 0) {
+        const int64_t n_out = (int64_t)h * w;
+        memcpy(x_out, cx, sizeof(double) * (size_t)(B * n_out * D));
+        if (metric_out) memcpy(metric_out, ck, sizeof(double) * (size_t)(B * n_out * Dm));
+        memcpy(sizes_out, cs, sizeof(int64_t) * (size_t)(B * n_out));
+        if (merged_map) memcpy(merged_map, tot_merged, sizeof(int32_t) * (size_t)(B * n_in));
+        if (kept_map)
+            for (int b = 0; b < B; ++b)
+                memcpy(kept_map + b * n_out, tot_kept + b * n_in, sizeof(int32_t) * (size_t)n_out);
+    }
+    free(cx); free(ck); free(cs); free(tot_merged); free(tot_kept);
+    return rc;
+}
+
+/* ------------------------------------------------------- value enhancement */
+
+/*
+ * Eq. 3 (Section 3.2): the values that enter attention are V + log(s), s =
+ * number of tokens merged into each token, added to every channel of the
+ * token's row.   v [rows, D], s [rows] -> out [rows, D], rounded to the I/O type.
+ */
+int oracle_value_enhance(const double *v, const int64_t *s, int64_t rows, int D, int round_mode, double *out)
+{
+    if (rows < 0 || D < 1) return -1;
+    for (int64_t r = 0; r < rows; ++r) {
+        if (s[r] < 1) return -1;
+        const double ls = log((double)s[r]);
+        for (int d = 0; d < D; ++d) out[r * D + d] = round_to_io(v[r * D + d] + ls, round_mode);
+    }
+    return 0;
 }
 
 /* --------------------------------------------------------------------- SPU */

@@ -276,3 +276,69 @@ def test_invalid_schedules(oracle):
         oracle.oim_merge(x, [(2, 1)])
     with pytest.raises(ValueError):
         oracle.oim_merge(rnd((1, 1, 1, 2)), [(W_AX, 1)])
+
+
+# ---------------------------------------------------------------- decisions on a separate metric (the keys of Section 3.1)
+
+@pytest.mark.parametrize("R", [1, 0])
+@pytest.mark.parametrize("passes", [[(W_AX, 2)], [(W_AX, 3), (H_AX, 2)], [(H_AX, 2), (W_AX, 2), (H_AX, 1)]])
+def test_keyed_with_metric_equal_to_tokens_is_the_plain_call(oracle, passes, R):
+    # the merge along the maps is written separately from the merge inside a pass: both must give the same numbers
+    x = rnd((2, 6, 7, 5), 21)
+    s = np.random.default_rng(22).integers(1, 4, (2, 6, 7))
+    for rm in (oracle.ROUND_NONE, oracle.ROUND_BF16):
+        a = oracle.oim_merge(x, passes, sizes=s, R=R, round_mode=rm)
+        b = oracle.oim_merge_keyed(x, x, passes, sizes=s, R=R, round_mode=rm)
+        for k in ("x", "sizes", "merged_map", "kept_map"):
+            np.testing.assert_array_equal(a[k], b[k])
+        np.testing.assert_array_equal(b["metric"], b["x"])
+
+
+def test_keyed_hand_case(oracle):
+    # line of three: sources 0 and 2, destination 1; one merge.  The keys say "0 is like 1" although the tokens
+    # themselves say "2 is like 1": the keys decide, the tokens follow.
+    x = np.array([[[[10.0, 0.0], [0.0, 1.0], [0.0, 1.1]]]])
+    keys = np.array([[[[1.0, 0.0, 0.0], [2.0, 0.0, 0.0], [0.0, 1.0, 0.0]]]])
+    r = oracle.oim_merge_keyed(x, keys, [(W_AX, 1)])
+    np.testing.assert_array_equal(r["sizes"], [[[2, 1]]])
+    np.testing.assert_allclose(r["x"], [[[[5.0, 0.5], [0.0, 1.1]]]])
+    np.testing.assert_allclose(r["metric"], [[[[1.5, 0.0, 0.0], [0.0, 1.0, 0.0]]]])
+    np.testing.assert_array_equal(r["merged_map"], [[0, 0, 1]])
+    np.testing.assert_array_equal(r["kept_map"], [[1, 2]])
+    plain = oracle.oim_merge(x, [(W_AX, 1)])
+    np.testing.assert_array_equal(plain["merged_map"], [[0, 1, 1]])           # the tokens alone would have merged 2 into 1
+
+
+def test_keyed_decisions_ignore_key_scale_and_conserve_mass(oracle):
+    rng = np.random.default_rng(23)
+    B, H, W, D, Dm = 2, 5, 8, 4, 6
+    x, keys = rng.standard_normal((B, H, W, D)), rng.standard_normal((B, H, W, Dm))
+    s = rng.integers(1, 5, (B, H, W))
+    passes = [(W_AX, 3)]
+    a = oracle.oim_merge_keyed(x, keys, passes, sizes=s, R=0)
+    scale = 2.0 ** rng.integers(-3, 4, (B, H, W, 1))                              # cosines do not see a positive factor per token
+    b = oracle.oim_merge_keyed(x, keys * scale, passes, sizes=s, R=0)
+    for k in ("x", "sizes", "merged_map", "kept_map"):
+        np.testing.assert_array_equal(a[k], b[k])
+    np.testing.assert_allclose((a["sizes"][..., None] * a["x"]).sum(axis=(1, 2)), (s[..., None] * x).sum(axis=(1, 2)), rtol=1e-12)
+    np.testing.assert_allclose((a["sizes"][..., None] * a["metric"]).sum(axis=(1, 2)), (s[..., None] * keys).sum(axis=(1, 2)), rtol=1e-12)
+    # and the decisions are those of a plain call on the keys
+    k_only = oracle.oim_merge(keys, passes, sizes=s, R=0)
+    np.testing.assert_array_equal(k_only["merged_map"], a["merged_map"])
+    np.testing.assert_array_equal(k_only["x"], a["metric"])
+
+
+# ---------------------------------------------------------------- value enhancement (Eq. 3)
+
+def test_value_enhance_closed_forms(oracle):
+    v = rnd((3, 4, 5), 31)
+    ones = np.ones((3, 4), np.int64)
+    np.testing.assert_array_equal(oracle.value_enhance(v, ones), v)                # log 1 = 0: unmerged tokens are untouched
+    s = np.array([[1, 2, 4, 8]] * 3)
+    out = oracle.value_enhance(v, s)
+    np.testing.assert_allclose(out - v, np.log(2.0) * np.array([0, 1, 2, 3])[None, :, None] * np.ones((3, 4, 5)), rtol=1e-13, atol=1e-15)
+    # softmax-weighted sum: adding log(s) to V shifts the attention output by sum_j A_ij log s_j (Eq. 2-3)
+    A = np.random.default_rng(32).random((4, 4)); A /= A.sum(1, keepdims=True)
+    np.testing.assert_allclose(A @ out[0], A @ v[0] + (A @ np.log(s[0]))[:, None], rtol=1e-12)
+    with pytest.raises(ValueError):
+        oracle.value_enhance(v, np.zeros((3, 4), np.int64))
