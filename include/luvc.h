@@ -128,6 +128,36 @@ luvc_status luvc_oim_merge_wide(const void* x, const int32_t* sizes_in,
                                 void* x_out, int32_t* sizes_out, int32_t* merged_map, int32_t* kept_map,
                                 void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/*
+ * OIM whose decisions are taken on a separate tensor (Section 3.1 counts the similarity cost in k, "the
+ * dimension of keys": similarity on the attention keys, merge applied to the tokens): as
+ * luvc_oim_merge_wide, except that the cosines are those of `metric` while x is merged along; the metric
+ * is merged the same way, so that the next pass (or the next layer) can go on with it.
+ *   metric      device [B,H,W,Dm] dtype
+ *   metric_out  device [B,H',W',Dm] dtype, or NULL
+ *   radius      1 = adjacent destinations, R > 1 = within 2R-1 positions, 0 = the whole line
+ * Runs on the general kernels (separate decision and merge launches).
+ */
+size_t luvc_oim_keyed_workspace_bytes(int B, int H, int W, int D, int Dm, luvc_dtype dtype,
+                                      const luvc_oim_pass* passes, int n_passes, int radius);
+luvc_status luvc_oim_merge_keyed(const void* x, const void* metric, const int32_t* sizes_in,
+                                 int B, int H, int W, int D, int Dm, luvc_dtype dtype,
+                                 const luvc_oim_pass* passes, int n_passes, int radius, int64_t target_tokens,
+                                 void* x_out, void* metric_out, int32_t* sizes_out,
+                                 int32_t* merged_map, int32_t* kept_map,
+                                 void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Value enhancement (Section 3.2, Eq. 3): O = A (V + log s) - this call forms V + log(s), s = number of
+ * tokens merged into each token (the size vector of Algorithm 1), added to every channel of the token's row.
+ *   v        device [rows,*] dtype, row r starts at v + r * v_stride (elements), v_stride >= D
+ *   sizes    device [rows] int32 >= 1 (values below 1 are read as 1)
+ *   out      device [rows,*] dtype with out_stride >= D; may be v itself (in place) when the strides agree
+ * The sum is formed in fp64 and rounded once to dtype.  Needs no workspace.
+ */
+luvc_status luvc_value_enhance(const void* v, const int32_t* sizes, int64_t rows, int D, int64_t v_stride,
+                               luvc_dtype dtype, void* out, int64_t out_stride, void* hip_stream);
+
 /* Bytes of workspace luvc_spu_score needs (0 on invalid arguments). */
 size_t luvc_spu_workspace_bytes(int B, int N, int D, luvc_dtype dtype, int sigma);
 

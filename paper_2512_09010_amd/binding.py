@@ -17,7 +17,8 @@ LUVC_OK, LUVC_ERR_INVALID_ARG, LUVC_ERR_UNSUPPORTED, LUVC_ERR_WORKSPACE, LUVC_ER
 LUVC_F32, LUVC_BF16 = 0, 1
 
 EXPORTS = ("luvc_version", "luvc_last_error", "luvc_oim_plan", "luvc_oim_workspace_bytes", "luvc_oim_merge",
-           "luvc_oim_wide_workspace_bytes", "luvc_oim_merge_wide", "luvc_spu_workspace_bytes", "luvc_spu_score", "luvc_keep_count", "luvc_spu_prune",
+           "luvc_oim_wide_workspace_bytes", "luvc_oim_merge_wide",
+           "luvc_oim_keyed_workspace_bytes", "luvc_oim_merge_keyed", "luvc_value_enhance", "luvc_spu_workspace_bytes", "luvc_spu_score", "luvc_keep_count", "luvc_spu_prune",
            "luvc_profile_start", "luvc_profile_stop", "luvc_profile_kernel")
 
 
@@ -57,6 +58,12 @@ def lib() -> ctypes.CDLL:
     L.luvc_oim_wide_workspace_bytes.restype = sz
     L.luvc_oim_merge_wide.argtypes = [vp, vp, i, i, i, i, i, pp, i, i, i64, vp, vp, vp, vp, vp, sz, vp]
     L.luvc_oim_merge_wide.restype = i
+    L.luvc_oim_keyed_workspace_bytes.argtypes = [i, i, i, i, i, i, pp, i, i]
+    L.luvc_oim_keyed_workspace_bytes.restype = sz
+    L.luvc_oim_merge_keyed.argtypes = [vp, vp, vp, i, i, i, i, i, i, pp, i, i, i64, vp, vp, vp, vp, vp, vp, sz, vp]
+    L.luvc_oim_merge_keyed.restype = i
+    L.luvc_value_enhance.argtypes = [vp, vp, i64, i, i64, i, vp, i64, vp]
+    L.luvc_value_enhance.restype = i
     L.luvc_spu_workspace_bytes.argtypes = [i, i, i, i, i]
     L.luvc_spu_workspace_bytes.restype = sz
     L.luvc_spu_score.argtypes = [vp, i, i, i, i64, i, i, i, vp, vp, sz, vp]
@@ -193,6 +200,50 @@ def luvc_oim_merge_wide(x, passes, radius: int, sizes=None, target_tokens: int =
     _check(lib().luvc_oim_merge_wide(_ptr(x), _ptr(sizes), B, H, W, D, code, parr, len(passes), int(radius), int(target_tokens),
                                      _ptr(out["x"]), _ptr(out["sizes"]), _ptr(out.get("merged_map")), _ptr(out.get("kept_map")),
                                      _ptr(workspace), workspace.numel(), _stream(stream)))
+    return out
+
+
+def luvc_oim_merge_keyed(x, metric, passes, radius: int = 1, sizes=None, target_tokens: int = 0, want_maps: bool = True,
+                         want_metric: bool = True, workspace=None, stream=None, out=None):
+    """Decisions on metric [B,H,W,Dm], merge applied to x [B,H,W,D].  Returns dict(x, metric, sizes, merged_map, kept_map)."""
+    import torch
+    assert x.is_cuda and x.is_contiguous() and x.dim() == 4 and metric.is_cuda and metric.is_contiguous() and metric.dim() == 4
+    assert metric.shape[:3] == x.shape[:3] and metric.dtype == x.dtype
+    B, H, W, D = x.shape
+    Dm = metric.shape[3]
+    code = _dtype_code(x)
+    parr = _passes(passes)
+    Ho, Wo = out_grid(H, W, passes)
+    need = lib().luvc_oim_keyed_workspace_bytes(B, H, W, D, Dm, code, parr, len(passes), int(radius))
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=x.device)
+    if out is None:
+        out = dict(
+            x=torch.empty((B, max(Ho, 0), max(Wo, 0), D), dtype=x.dtype, device=x.device),
+            metric=torch.empty((B, max(Ho, 0), max(Wo, 0), Dm), dtype=x.dtype, device=x.device) if want_metric else None,
+            sizes=torch.empty((B, max(Ho, 0), max(Wo, 0)), dtype=torch.int32, device=x.device),
+            merged_map=torch.empty((B, H * W), dtype=torch.int32, device=x.device) if want_maps else None,
+            kept_map=torch.empty((B, max(Ho, 0) * max(Wo, 0)), dtype=torch.int32, device=x.device) if want_maps else None,
+        )
+    if sizes is not None:
+        assert sizes.is_cuda and sizes.dtype == torch.int32 and sizes.is_contiguous() and sizes.numel() == B * H * W
+    _check(lib().luvc_oim_merge_keyed(_ptr(x), _ptr(metric), _ptr(sizes), B, H, W, D, Dm, code, parr, len(passes), int(radius),
+                                      int(target_tokens), _ptr(out["x"]), _ptr(out.get("metric")), _ptr(out["sizes"]),
+                                      _ptr(out.get("merged_map")), _ptr(out.get("kept_map")),
+                                      _ptr(workspace), workspace.numel(), _stream(stream)))
+    return out
+
+
+def luvc_value_enhance(v, sizes, stream=None, out=None):
+    """v: CUDA tensor [..., D] (last dim contiguous, rows evenly strided), sizes int32 [...]: returns v + log(sizes)."""
+    import torch
+    assert v.is_cuda and v.stride(-1) == 1 and sizes.is_cuda and sizes.dtype == torch.int32 and sizes.is_contiguous()
+    D = v.shape[-1]
+    rows = sizes.numel()
+    assert v.numel() == rows * D and v.is_contiguous()
+    if out is None:
+        out = torch.empty_like(v)
+    _check(lib().luvc_value_enhance(_ptr(v), _ptr(sizes), rows, D, D, _dtype_code(v), _ptr(out), D, _stream(stream)))
     return out
 
 

@@ -312,6 +312,132 @@ luvc_status luvc_oim_merge_wide(const void* x, const int32_t* sizes_in, int B, i
                           workspace, workspace_bytes, hip_stream);
 }
 
+// ---- OIM decided on a separate metric tensor (general kernels only: decisions and merge are separate stages)
+struct KeyedLayout {
+    OimLayout base;
+    size_t mbuf[2], bytes;          // ping-pong buffers of the merged metric between passes
+};
+
+static KeyedLayout keyed_layout(int B, int D, int Dm, luvc_dtype dt, const OimPlan& pl, const luvc_oim_pass* passes, int radius)
+{
+    KeyedLayout K;
+    // the wide-matching scratch is sized by oim_layout when radius != 1; a radius of 1 needs none
+    K.base = oim_layout(B, D, dt, pl, passes, radius);
+    size_t off = K.base.bytes;
+    size_t tok[2] = {0, 0};
+    for (int i = 0; i < pl.n; ++i) {              // the metric of the last pass may be wanted as well (metric_out == NULL)
+        const size_t t = (size_t)B * pl.h[i + 1] * pl.w[i + 1];
+        if (t > tok[i & 1]) tok[i & 1] = t;
+    }
+    for (int j = 0; j < 2; ++j) { K.mbuf[j] = off; off += align_up(tok[j] * Dm * esize(dt)); }
+    K.bytes = off;
+    return K;
+}
+
+static bool keyed_args_ok(int radius, int Dm)
+{
+    if (radius < 0) { set_error("radius must be 0 (whole line) or positive"); return false; }
+    if (Dm < 1) { set_error("Dm must be positive (got %d)", Dm); return false; }
+    return true;
+}
+
+size_t luvc_oim_keyed_workspace_bytes(int B, int H, int W, int D, int Dm, luvc_dtype dtype, const luvc_oim_pass* passes, int n_passes, int radius)
+{
+    OimPlan pl;
+    if (!dtype_ok(dtype) || radius < 0 || Dm < 1 || !walk_schedule(B, H, W, D, passes, n_passes, &pl)) return 0;
+    return keyed_layout(B, D, Dm, dtype, pl, passes, radius).bytes;
+}
+
+luvc_status luvc_oim_merge_keyed(const void* x, const void* metric, const int32_t* sizes_in,
+                                 int B, int H, int W, int D, int Dm, luvc_dtype dtype,
+                                 const luvc_oim_pass* passes, int n_passes, int radius, int64_t target_tokens,
+                                 void* x_out, void* metric_out, int32_t* sizes_out, int32_t* merged_map, int32_t* kept_map,
+                                 void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    if (!dtype_ok(dtype)) { set_error("unknown dtype %d", (int)dtype); return LUVC_ERR_INVALID_ARG; }
+    if (!x || !metric || !x_out || !sizes_out) { set_error("x, metric, x_out and sizes_out must not be NULL"); return LUVC_ERR_INVALID_ARG; }
+    if (!keyed_args_ok(radius, Dm)) return LUVC_ERR_INVALID_ARG;
+    OimPlan pl;
+    if (!walk_schedule(B, H, W, D, passes, n_passes, &pl)) return LUVC_ERR_INVALID_ARG;
+    const int Ho = pl.h[pl.n], Wo = pl.w[pl.n];
+    if (target_tokens != 0 && target_tokens != (int64_t)Ho * Wo) {
+        set_error("schedule ends at %dx%d = %lld tokens, target is %lld", Ho, Wo, (long long)Ho * Wo, (long long)target_tokens);
+        return LUVC_ERR_INVALID_ARG;
+    }
+    if (radius != 1) {
+        for (int i = 0; i < pl.n; ++i)
+            if ((passes[i].axis ? pl.w[i] : pl.h[i]) > kMaxWideLineLen) {
+                set_error("pass %d: wide matching supports lines of at most %d tokens", i, kMaxWideLineLen);
+                return LUVC_ERR_UNSUPPORTED;
+            }
+        if ((int64_t)H * W * Dm * (int64_t)esize(dtype) >= ((int64_t)1 << 31)) {
+            set_error("wide matching supports grids of less than 2 GiB per image");
+            return LUVC_ERR_UNSUPPORTED;
+        }
+    }
+    const KeyedLayout K = keyed_layout(B, D, Dm, dtype, pl, passes, radius);
+    const OimLayout& L = K.base;
+    if (!workspace_ok(workspace, workspace_bytes, K.bytes)) return LUVC_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)hip_stream;
+    char* ws = (char*)workspace;
+    const size_t es = esize(dtype);
+    const bool vec_x = ((size_t)D * es) % 16 == 0 && (uintptr_t)x % 16 == 0 && (uintptr_t)x_out % 16 == 0;
+    const bool vec_m = ((size_t)Dm * es) % 16 == 0 && (uintptr_t)metric % 16 == 0 && (!metric_out || (uintptr_t)metric_out % 16 == 0);
+    OimScratch sc;
+    sc.n2 = (double*)(ws + L.n2);
+    sc.dn = (double*)(ws + L.dn);
+    sc.anchor = (int32_t*)(ws + L.anchor);
+    sc.absorb = (int32_t*)(ws + L.absorb);
+    double* G = (double*)(ws + L.gram);
+    int32_t* src_dest = (int32_t*)(ws + L.srcdest);
+
+    const void *cur_x = x, *cur_m = metric;
+    const int32_t* cur_s = sizes_in;
+    const int32_t* cur_k = nullptr;
+    const int32_t* maps[kMaxPasses];
+    int32_t n_in[kMaxPasses];
+    for (int i = 0; i < pl.n; ++i) {
+        const bool last = i + 1 == pl.n;
+        const int h = pl.h[i], w = pl.w[i], axis = passes[i].axis, m = passes[i].m;
+        void* ox = last ? x_out : (void*)(ws + L.xbuf[i & 1]);
+        void* om = (last && metric_out) ? metric_out : (void*)(ws + K.mbuf[i & 1]);
+        int32_t* os = last ? sizes_out : (int32_t*)(ws + L.sbuf[i & 1]);
+        int32_t* ok = last ? kept_map : (int32_t*)(ws + L.kbuf[i & 1]);
+        int32_t* pm = (pl.n == 1 && merged_map) ? merged_map : (int32_t*)(ws + L.maps[i]);
+        maps[i] = pm;
+        n_in[i] = h * w;
+        luvc_status rc;
+        if (radius == 1) rc = oim_general_decide(cur_m, B, h, w, Dm, dtype, axis, m, vec_m, pm, sc, st);
+        else             rc = oim_wide_decide(cur_m, B, h, w, Dm, dtype, axis, m, radius, vec_m, pm, sc, G, src_dest, st);
+        if (rc != LUVC_OK) return rc;
+        if (radius == 1) rc = oim_general_apply(cur_x, cur_s, B, h, w, D, dtype, axis, m, vec_x, ox, os, cur_k, ok, sc, st);
+        else             rc = oim_wide_apply(cur_x, cur_s, B, h, w, D, dtype, axis, m, vec_x, ox, os, cur_k, ok, sc, src_dest, st);
+        if (rc != LUVC_OK) return rc;
+        if (!last || metric_out) {               // the metric follows its own decisions (sizes and anchors are written again, same values)
+            if (radius == 1) rc = oim_general_apply(cur_m, cur_s, B, h, w, Dm, dtype, axis, m, vec_m, om, os, nullptr, nullptr, sc, st);
+            else             rc = oim_wide_apply(cur_m, cur_s, B, h, w, Dm, dtype, axis, m, vec_m, om, os, nullptr, nullptr, sc, src_dest, st);
+            if (rc != LUVC_OK) return rc;
+        }
+        cur_x = ox;
+        cur_m = om;
+        cur_s = os;
+        cur_k = ok;
+    }
+    if (merged_map && pl.n > 1) return oim_compose(maps, n_in, pl.n, B, H * W, merged_map, st);
+    return LUVC_OK;
+}
+
+luvc_status luvc_value_enhance(const void* v, const int32_t* sizes, int64_t rows, int D, int64_t v_stride, luvc_dtype dtype,
+                               void* out, int64_t out_stride, void* hip_stream)
+{
+    if (!dtype_ok(dtype)) { set_error("unknown dtype %d", (int)dtype); return LUVC_ERR_INVALID_ARG; }
+    if (!v || !sizes || !out) { set_error("v, sizes and out must not be NULL"); return LUVC_ERR_INVALID_ARG; }
+    if (rows < 1 || D < 1) { set_error("rows and D must be positive"); return LUVC_ERR_INVALID_ARG; }
+    if (v_stride < D || out_stride < D) { set_error("row strides must be at least D=%d", D); return LUVC_ERR_INVALID_ARG; }
+    if (rows > ((int64_t)1 << 40)) { set_error("too many rows"); return LUVC_ERR_UNSUPPORTED; }
+    return value_enhance_run(v, sizes, rows, D, v_stride, out_stride, dtype, out, (hipStream_t)hip_stream);
+}
+
 size_t luvc_spu_workspace_bytes(int B, int N, int D, luvc_dtype dtype, int sigma)
 {
     if (!dtype_ok(dtype) || B < 1 || N < 1 || D < 1 || sigma < 0 || sigma > N / 2 || N > kSpuMaxN) return 0;

@@ -238,28 +238,44 @@ oim_compose_merged(PassMaps pm, int64_t total, int n_first, int32_t* __restrict_
 }
 
 // ------------------------------------------------------------------ host side
-template <typename T>
-static luvc_status run_pass(const T* x, const int32_t* sizes_in, int B, int H, int W, int D, int axis, int m,
-                            bool vec, T* x_out, int32_t* sizes_out, int32_t* pass_map,
-                            const int32_t* kept_prev, int32_t* kept_out,
-                            const OimScratch& ws, hipStream_t st)
+luvc_status oim_norms(const void* x, int B, int H, int W, int D, luvc_dtype dt, int axis, bool vec,
+                      const OimScratch& ws, hipStream_t st);
+
+// A pass in two stages, so that the decisions can be taken on one tensor (the metric) and applied to another.
+luvc_status oim_general_decide(const void* metric, int B, int H, int W, int Dm, luvc_dtype dt, int axis, int m, bool vec,
+                               int32_t* pass_map, const OimScratch& ws, hipStream_t st)
 {
-    const int64_t n_tok = (int64_t)B * H * W;
     const int len = axis ? W : H, nlines = axis ? H : W, n_src = (len + 1) / 2;
-    const int Ho = axis ? H : H - m, Wo = axis ? W - m : W;
-    const int64_t n_out = (int64_t)B * Ho * Wo;
-    const unsigned g1 = (unsigned)((n_tok * 64 + 255) / 256);
-    if (vec) LUVC_LAUNCH("oim_pairdot", (oim_pairdot<T, true>), dim3(g1), dim3(256), 0, st, x, ws.n2, ws.dn, n_tok, H, W, D, axis);
-    else     LUVC_LAUNCH("oim_pairdot", (oim_pairdot<T, false>), dim3(g1), dim3(256), 0, st, x, ws.n2, ws.dn, n_tok, H, W, D, axis);
+    const luvc_status rc = oim_norms(metric, B, H, W, Dm, dt, axis, vec, ws, st);
+    if (rc != LUVC_OK) return rc;
     const size_t lds = sizeof(double) * n_src + sizeof(int) * n_src + sizeof(int) * (256 + 1) + (size_t)len + 16;
     LUVC_LAUNCH("oim_decide", oim_decide, dim3((unsigned)(B * nlines)), dim3(256), lds, st, ws.n2, ws.dn, H, W, axis, m,
                        pass_map, ws.anchor, ws.absorb);
+    return check_launch("oim pass (decisions)");
+}
+
+template <typename T>
+static luvc_status run_apply(const T* x, const int32_t* sizes_in, int B, int H, int W, int D, int axis, int m,
+                             bool vec, T* x_out, int32_t* sizes_out, const int32_t* kept_prev, int32_t* kept_out,
+                             const OimScratch& ws, hipStream_t st)
+{
+    const int Ho = axis ? H : H - m, Wo = axis ? W - m : W;
+    const int64_t n_out = (int64_t)B * Ho * Wo;
     const unsigned g3 = (unsigned)((n_out * 64 + 255) / 256);
     if (vec) LUVC_LAUNCH("oim_merge", (oim_merge<T, true>), dim3(g3), dim3(256), 0, st, x, sizes_in, ws.anchor, ws.absorb, kept_prev,
                                 n_out, H * W, Ho * Wo, W, D, axis, x_out, sizes_out, kept_out);
     else     LUVC_LAUNCH("oim_merge", (oim_merge<T, false>), dim3(g3), dim3(256), 0, st, x, sizes_in, ws.anchor, ws.absorb, kept_prev,
                                 n_out, H * W, Ho * Wo, W, D, axis, x_out, sizes_out, kept_out);
-    return check_launch("oim pass");
+    return check_launch("oim pass (merge)");
+}
+
+luvc_status oim_general_apply(const void* x, const int32_t* sizes_in, int B, int H, int W, int D, luvc_dtype dt, int axis, int m,
+                              bool vec, void* x_out, int32_t* sizes_out, const int32_t* kept_prev, int32_t* kept_out,
+                              const OimScratch& ws, hipStream_t st)
+{
+    if (dt == LUVC_F32)
+        return run_apply<float>((const float*)x, sizes_in, B, H, W, D, axis, m, vec, (float*)x_out, sizes_out, kept_prev, kept_out, ws, st);
+    return run_apply<bf16_t>((const bf16_t*)x, sizes_in, B, H, W, D, axis, m, vec, (bf16_t*)x_out, sizes_out, kept_prev, kept_out, ws, st);
 }
 
 luvc_status oim_norms(const void* x, int B, int H, int W, int D, luvc_dtype dt, int axis, bool vec,
@@ -282,11 +298,9 @@ luvc_status oim_general_pass(const void* x, const int32_t* sizes_in, int B, int 
                              const int32_t* kept_prev, int32_t* kept_out,
                              const OimScratch& ws, hipStream_t st)
 {
-    if (dt == LUVC_F32)
-        return run_pass<float>((const float*)x, sizes_in, B, H, W, D, axis, m, vec, (float*)x_out, sizes_out, pass_map,
-                               kept_prev, kept_out, ws, st);
-    return run_pass<bf16_t>((const bf16_t*)x, sizes_in, B, H, W, D, axis, m, vec, (bf16_t*)x_out, sizes_out, pass_map,
-                            kept_prev, kept_out, ws, st);
+    const luvc_status rc = oim_general_decide(x, B, H, W, D, dt, axis, m, vec, pass_map, ws, st);
+    if (rc != LUVC_OK) return rc;
+    return oim_general_apply(x, sizes_in, B, H, W, D, dt, axis, m, vec, x_out, sizes_out, kept_prev, kept_out, ws, st);
 }
 
 luvc_status oim_compose(const int32_t* const* maps, const int32_t* n_in, int n, int B, int n_first,

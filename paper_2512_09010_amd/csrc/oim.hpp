@@ -34,6 +34,22 @@ luvc_status oim_wide_pass(const void* x, const int32_t* sizes_in, int B, int H, 
                           const int32_t* kept_prev, int32_t* kept_out,
                           const OimScratch& ws, double* G, int32_t* src_dest, hipStream_t st);
 
+// The two stages of a pass on their own: decisions on one tensor (`metric`), merge applied to another.
+luvc_status oim_general_decide(const void* metric, int B, int H, int W, int Dm, luvc_dtype dt, int axis, int m, bool vec,
+                               int32_t* pass_map, const OimScratch& ws, hipStream_t st);
+luvc_status oim_general_apply(const void* x, const int32_t* sizes_in, int B, int H, int W, int D, luvc_dtype dt, int axis, int m,
+                              bool vec, void* x_out, int32_t* sizes_out, const int32_t* kept_prev, int32_t* kept_out,
+                              const OimScratch& ws, hipStream_t st);
+luvc_status oim_wide_decide(const void* metric, int B, int H, int W, int Dm, luvc_dtype dt, int axis, int m, int radius, bool vec,
+                            int32_t* pass_map, const OimScratch& ws, double* G, int32_t* src_dest, hipStream_t st);
+luvc_status oim_wide_apply(const void* x, const int32_t* sizes_in, int B, int H, int W, int D, luvc_dtype dt, int axis, int m, bool vec,
+                           void* x_out, int32_t* sizes_out, const int32_t* kept_prev, int32_t* kept_out,
+                           const OimScratch& ws, const int32_t* src_dest, hipStream_t st);
+
+// Eq. 3 of the paper: out = v + log(s) on every channel of a row (value.hip)
+luvc_status value_enhance_run(const void* v, const int32_t* sizes, int64_t rows, int D, int64_t v_stride, int64_t out_stride,
+                              luvc_dtype dt, void* out, hipStream_t st);
+
 // Fused pass for m = ceil(len/2) (oim_fast.hip); `vec` = rows are 16-byte aligned.
 bool oim_halve_supported(int H, int W, int D, luvc_dtype dt, int axis, int m, bool vec);
 luvc_status oim_halve_pass(const void* x, const int32_t* sizes_in, int B, int H, int W, int D, luvc_dtype dt, int axis,

@@ -13,8 +13,6 @@
 //                  position), the m best sources (tie -> lower position), survivor layout, maps;
 //   oim_merge_wide one wavefront per surviving token: copy, or size-weighted mean of the destination
 //                  and all sources folded into it (ascending position, fp64, one rounding).
-#include <type_traits>
-
 #include "common.hpp"
 #include "oim.hpp"
 
@@ -370,31 +368,53 @@ size_t oim_wide_srcdest_bytes(int B, int H, int W, int axis)
 }
 
 template <typename T>
-static luvc_status run_wide(const T* x, const int32_t* sizes_in, int B, int H, int W, int D, int axis, int m, int radius,
-                            bool vec, T* x_out, int32_t* sizes_out, int32_t* pass_map,
-                            const int32_t* kept_prev, int32_t* kept_out,
-                            const OimScratch& ws, double* G, int32_t* src_dest, hipStream_t st)
+static luvc_status run_wide_decide(const T* metric, int B, int H, int W, int Dm, int axis, int m, int radius, bool vec,
+                                   int32_t* pass_map, const OimScratch& ws, double* G, int32_t* src_dest, hipStream_t st)
 {
     const int len = axis ? W : H, nlines = axis ? H : W, n_src = (len + 1) / 2, n_dst = len / 2;
-    const int Ho = axis ? H : H - m, Wo = axis ? W - m : W;
-    const int64_t n_out = (int64_t)B * Ho * Wo;
     if (n_dst > 0) {
         const int tiles_s = (n_src + 15) / 16, tiles_d = (n_dst + 15) / 16;
         const int64_t n_tiles = (int64_t)B * nlines * tiles_s * tiles_d;
         if (n_tiles >= ((int64_t)1 << 31)) { set_error("wide matching: too many 16 x 16 tiles in one pass"); return LUVC_ERR_UNSUPPORTED; }
         const unsigned g1 = (unsigned)((n_tiles + 3) / 4);
-        if (vec) LUVC_LAUNCH("oim_line_gram", (oim_line_gram<T, true>), dim3(g1), dim3(256), 0, st, x, G, ws.n2, H, W, D, axis, n_tiles, tiles_s, tiles_d);
-        else     LUVC_LAUNCH("oim_line_gram", (oim_line_gram<T, false>), dim3(g1), dim3(256), 0, st, x, G, ws.n2, H, W, D, axis, n_tiles, tiles_s, tiles_d);
+        if (vec) LUVC_LAUNCH("oim_line_gram", (oim_line_gram<T, true>), dim3(g1), dim3(256), 0, st, metric, G, ws.n2, H, W, Dm, axis, n_tiles, tiles_s, tiles_d);
+        else     LUVC_LAUNCH("oim_line_gram", (oim_line_gram<T, false>), dim3(g1), dim3(256), 0, st, metric, G, ws.n2, H, W, Dm, axis, n_tiles, tiles_s, tiles_d);
     }
     const size_t lds = sizeof(double) * (size_t)(n_src + len) + sizeof(int) * (size_t)(n_src + len + 256 + 1) + (size_t)len + 16;
     LUVC_LAUNCH("oim_decide_wide", oim_decide_wide, dim3((unsigned)(B * nlines)), dim3(256), lds, st, ws.n2, G, H, W, axis, m, radius,
                 pass_map, ws.anchor, src_dest);
+    return check_launch("oim pass (wide matching, decisions)");
+}
+
+template <typename T>
+static luvc_status run_wide_apply(const T* x, const int32_t* sizes_in, int B, int H, int W, int D, int axis, int m, bool vec,
+                                  T* x_out, int32_t* sizes_out, const int32_t* kept_prev, int32_t* kept_out,
+                                  const OimScratch& ws, const int32_t* src_dest, hipStream_t st)
+{
+    const int Ho = axis ? H : H - m, Wo = axis ? W - m : W;
+    const int64_t n_out = (int64_t)B * Ho * Wo;
     const unsigned g3 = (unsigned)((n_out * 64 + 255) / 256);
     if (vec) LUVC_LAUNCH("oim_merge_wide", (oim_merge_wide<T, true>), dim3(g3), dim3(256), 0, st, x, sizes_in, ws.anchor, src_dest, kept_prev,
                          n_out, H, W, Ho, Wo, D, axis, x_out, sizes_out, kept_out);
     else     LUVC_LAUNCH("oim_merge_wide", (oim_merge_wide<T, false>), dim3(g3), dim3(256), 0, st, x, sizes_in, ws.anchor, src_dest, kept_prev,
                          n_out, H, W, Ho, Wo, D, axis, x_out, sizes_out, kept_out);
-    return check_launch("oim pass (wide matching)");
+    return check_launch("oim pass (wide matching, merge)");
+}
+
+luvc_status oim_wide_decide(const void* metric, int B, int H, int W, int Dm, luvc_dtype dt, int axis, int m, int radius, bool vec,
+                            int32_t* pass_map, const OimScratch& ws, double* G, int32_t* src_dest, hipStream_t st)
+{
+    if (dt == LUVC_F32) return run_wide_decide<float>((const float*)metric, B, H, W, Dm, axis, m, radius, vec, pass_map, ws, G, src_dest, st);
+    return run_wide_decide<bf16_t>((const bf16_t*)metric, B, H, W, Dm, axis, m, radius, vec, pass_map, ws, G, src_dest, st);
+}
+
+luvc_status oim_wide_apply(const void* x, const int32_t* sizes_in, int B, int H, int W, int D, luvc_dtype dt, int axis, int m, bool vec,
+                           void* x_out, int32_t* sizes_out, const int32_t* kept_prev, int32_t* kept_out,
+                           const OimScratch& ws, const int32_t* src_dest, hipStream_t st)
+{
+    if (dt == LUVC_F32)
+        return run_wide_apply<float>((const float*)x, sizes_in, B, H, W, D, axis, m, vec, (float*)x_out, sizes_out, kept_prev, kept_out, ws, src_dest, st);
+    return run_wide_apply<bf16_t>((const bf16_t*)x, sizes_in, B, H, W, D, axis, m, vec, (bf16_t*)x_out, sizes_out, kept_prev, kept_out, ws, src_dest, st);
 }
 
 luvc_status oim_wide_pass(const void* x, const int32_t* sizes_in, int B, int H, int W, int D, luvc_dtype dt,
@@ -402,11 +422,9 @@ luvc_status oim_wide_pass(const void* x, const int32_t* sizes_in, int B, int H, 
                           const int32_t* kept_prev, int32_t* kept_out,
                           const OimScratch& ws, double* G, int32_t* src_dest, hipStream_t st)
 {
-    if (dt == LUVC_F32)
-        return run_wide<float>((const float*)x, sizes_in, B, H, W, D, axis, m, radius, vec, (float*)x_out, sizes_out, pass_map,
-                               kept_prev, kept_out, ws, G, src_dest, st);
-    return run_wide<bf16_t>((const bf16_t*)x, sizes_in, B, H, W, D, axis, m, radius, vec, (bf16_t*)x_out, sizes_out, pass_map,
-                            kept_prev, kept_out, ws, G, src_dest, st);
+    const luvc_status rc = oim_wide_decide(x, B, H, W, D, dt, axis, m, radius, vec, pass_map, ws, G, src_dest, st);
+    if (rc != LUVC_OK) return rc;
+    return oim_wide_apply(x, sizes_in, B, H, W, D, dt, axis, m, vec, x_out, sizes_out, kept_prev, kept_out, ws, src_dest, st);
 }
 
 }  // namespace luvc

@@ -1,0 +1,93 @@
+"""GPU parity: luvc_oim_merge_keyed (decisions on the keys, merge applied to the tokens; Section 3.1 counts the
+similarity in "the dimension of keys") and luvc_value_enhance (Eq. 3, V + log s) against the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2512_09010_amd import binding as lv
+from paper_2512_09010_amd import workloads as wl
+from gpu_util import OIM_MARGIN, RTOL, assert_close, round_mode, to_dev, to_host_f64
+
+pytestmark = pytest.mark.gpu
+W_AX, H_AX = 1, 0
+
+
+def run_keyed(oracle, x_io, k_io, dtype, passes, radius, sizes=None, tag=""):
+    print(f"[oim keyed] {tag} x={x_io.shape} keys={k_io.shape} dtype={dtype} passes={passes} radius={radius}", flush=True)
+    ref = oracle.oim_merge_keyed(wl.widen(x_io, dtype), wl.widen(k_io, dtype), passes, sizes=sizes, R=radius,
+                                 round_mode=round_mode(oracle, dtype))
+    s_dev = None if sizes is None else torch.from_numpy(np.ascontiguousarray(sizes, dtype=np.int32)).cuda()
+    out = lv.luvc_oim_merge_keyed(to_dev(x_io, dtype), to_dev(k_io, dtype), passes, radius, sizes=s_dev)
+    torch.cuda.synchronize()
+    if not (ref["margin"] > OIM_MARGIN or ref["margin"] == 0.0):
+        pytest.skip(f"decision margin {ref['margin']:.3e} below {OIM_MARGIN}: maps not unique")
+    np.testing.assert_array_equal(out["sizes"].cpu().numpy().astype(np.int64), ref["sizes"])
+    np.testing.assert_array_equal(out["merged_map"].cpu().numpy(), ref["merged_map"])
+    np.testing.assert_array_equal(out["kept_map"].cpu().numpy(), ref["kept_map"])
+    for name in ("x", "metric"):
+        got = to_host_f64(out[name])
+        assert_close(got, ref[name], RTOL[dtype], f"{tag} {name}")
+        if dtype == "bf16":
+            np.testing.assert_array_equal(got, ref[name])
+    return out, ref
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("radius", [1, 0, 2])
+@pytest.mark.parametrize("B,H,W,D,Dm,passes", [
+    (1, 1, 3, 8, 8, [(W_AX, 1)]),
+    (2, 6, 9, 40, 16, [(W_AX, 2), (H_AX, 2)]),                  # merge number 2, keys narrower than the tokens
+    (1, 9, 6, 24, 64, [(H_AX, 2), (W_AX, 2), (H_AX, 1)]),       # keys wider than the tokens, three passes
+    (2, 4, 5, 33, 7, [(W_AX, 3), (H_AX, 0)]),                   # rows that are not 16-byte multiples, m = 0 pass
+    (1, 12, 12, 520, 72, [(W_AX, 6), (H_AX, 6)]),               # halving passes on the general kernels
+])
+def test_keyed_small_random(oracle, dtype, radius, B, H, W, D, Dm, passes):
+    rng = np.random.default_rng(B * 1000 + H * 100 + W * 10 + D + Dm + radius)
+    x = wl.cast_io(rng.standard_normal((B, H, W, D)).astype(np.float32), dtype)
+    keys = wl.cast_io(rng.standard_normal((B, H, W, Dm)).astype(np.float32), dtype)
+    run_keyed(oracle, x, keys, dtype, passes, radius, tag="random")
+    sizes = rng.integers(1, 6, (B, H, W))
+    run_keyed(oracle, x, keys, dtype, passes, radius, sizes=sizes, tag="random+sizes")
+
+
+def test_keyed_with_the_tokens_as_keys_is_the_plain_call():
+    rng = np.random.default_rng(17)
+    x = to_dev(wl.cast_io(wl.smooth_field(rng, 2, 8, 10, 64, 2.0) + 0.1 * rng.standard_normal((2, 8, 10, 64)).astype(np.float32), "bf16"), "bf16")
+    passes = [(W_AX, 2), (H_AX, 2)]
+    for radius in (1, 0):
+        a = lv.luvc_oim_merge_keyed(x, x, passes, radius)
+        b = lv.luvc_oim_merge_wide(x, passes, radius)
+        torch.cuda.synchronize()
+        for k in ("x", "sizes", "merged_map", "kept_map"):
+            assert torch.equal(a[k], b[k]), (radius, k)
+        assert torch.equal(a["metric"], a["x"])
+
+
+def test_keyed_without_metric_output(oracle):
+    rng = np.random.default_rng(18)
+    x = wl.cast_io(rng.standard_normal((1, 6, 6, 32)).astype(np.float32), "bf16")
+    keys = wl.cast_io(rng.standard_normal((1, 6, 6, 16)).astype(np.float32), "bf16")
+    passes = [(W_AX, 2), (H_AX, 2)]
+    ref = oracle.oim_merge_keyed(wl.widen(x, "bf16"), wl.widen(keys, "bf16"), passes, R=0, round_mode=oracle.ROUND_BF16)
+    out = lv.luvc_oim_merge_keyed(to_dev(x, "bf16"), to_dev(keys, "bf16"), passes, 0, want_metric=False, want_maps=False)
+    torch.cuda.synchronize()
+    assert out["metric"] is None
+    np.testing.assert_array_equal(to_host_f64(out["x"]), ref["x"])
+
+
+@pytest.mark.parametrize("dtype,shape", [("f32", (3, 7, 33)), ("bf16", (2, 64, 1280)), ("bf16", (5, 3, 10)), ("f32", (1, 19, 256))])
+def test_value_enhance(oracle, dtype, shape):
+    rng = np.random.default_rng(sum(shape))
+    v = wl.cast_io(rng.standard_normal(shape).astype(np.float32), dtype)
+    sizes = rng.integers(1, 40, shape[:-1])
+    sizes.flat[0] = 1
+    ref = oracle.value_enhance(wl.widen(v, dtype), sizes, round_mode=round_mode(oracle, dtype))
+    out = lv.luvc_value_enhance(to_dev(v, dtype), torch.from_numpy(sizes.astype(np.int32)).cuda())
+    torch.cuda.synchronize()
+    got = to_host_f64(out)
+    # the sum is formed in fp64 and rounded once on both sides; the two logarithms may differ in their last fp64 bit,
+    # which can only move a result that sits on a rounding boundary: one unit of the storage type at most
+    ulp = 2.0 ** -7 if dtype == "bf16" else 2.0 ** -23
+    assert (np.abs(got - ref) <= ulp * np.abs(ref)).all()
+    assert (got == ref).mean() > 0.999
+    np.testing.assert_array_equal(got.reshape(-1, shape[-1])[0], wl.widen(v, dtype).reshape(-1, shape[-1])[0])     # s = 1: untouched
