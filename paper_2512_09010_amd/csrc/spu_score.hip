@@ -151,16 +151,22 @@ spu_finish(const float* __restrict__ partial, int N, int n_tiles, int64_t total,
 }
 
 // ------------------------------------------------------------------ one launch for small samples
-// Workgroup (tile, b): 64 channels (lanes) x 16 wavefronts.  Forward: the wavefronts split the tokens
-// (n = wave, wave + 16, ...), each accumulates kDfBins bins at a time, the 16 partial sums of a bin meet
-// in LDS and are added in wavefront order into F = g_k (C_k, S_k).  Inverse: the wavefronts split the
-// tokens again, kDfTok tokens per register block; energies summed over the lanes; tiles summed by the
-// hand-over of spu_tiles.hpp.
-constexpr int kDfWaves = 16, kDfBins = 6, kDfTok = 4;
+// Workgroup (tile, b): 64 channels (lanes) x 16 wavefronts.  The twiddles of every (token, bin) pair sit in an
+// LDS table T[n][k] = (cos, sin)(2 pi k n / N), k < KP (the pass band padded to a multiple of kDfBins), so that
+// a token's kDfBins twiddles are three 16-byte reads and no index arithmetic is left in the loops.
+// Forward: the wavefronts split the tokens (n = wave, wave + 16, ...), each accumulates kDfBins bins at a time,
+// the 16 partial sums of a bin meet in LDS and are added in wavefront order into F = g_k (C_k, S_k).  Inverse:
+// the wavefronts split the tokens again, kDfTok tokens per register block; energies summed over the lanes;
+// tiles summed by the hand-over of spu_tiles.hpp.
+constexpr int kDfWaves = 16, kDfBins = 6, kDfTok = 4, kDfChunk = 16;
+
+static int dense_fused_kp(int sigma) { return (sigma + 1 + kDfBins - 1) / kDfBins * kDfBins; }
 
 static size_t dense_fused_lds(int N, int sigma)
 {
-    return sizeof(float2) * (size_t)N + sizeof(float) * ((size_t)(sigma + 1) * 128 + (size_t)(sigma + 1) + (size_t)kDfWaves * kDfBins * 128);
+    const size_t kp = (size_t)dense_fused_kp(sigma);
+    const size_t red = sizeof(float) * (size_t)kDfWaves * kDfBins * 128;           // also holds the N-entry table while T is built
+    return sizeof(float2) * (size_t)N * kp + sizeof(float) * (kp * 128 + kp) + (red > sizeof(float2) * (size_t)N ? red : sizeof(float2) * (size_t)N);
 }
 
 template <typename T>
@@ -170,11 +176,13 @@ spu_dense_fused(const T* __restrict__ x, int N, int D, int64_t row_stride, int s
                 float* __restrict__ scores)
 {
     using tr = io_traits<T>;
-    extern __shared__ float2 dsm[];
-    float2* tw = dsm;                                               // [N]  (cos, sin)(2 pi i / N)
-    float* F = reinterpret_cast<float*>(tw + N);                    // [sigma + 1][2][64]  g_k C_k, g_k S_k
-    float* gk = F + (size_t)(sigma + 1) * 128;                      // [sigma + 1]
-    float* red = gk + (sigma + 1);                                  // [16][kDfBins][2][64]
+    extern __shared__ __align__(16) float2 dsm[];
+    const int KP = (sigma + 1 + kDfBins - 1) / kDfBins * kDfBins;
+    float2* Tt = dsm;                                               // [N][KP]  (cos, sin)(2 pi k n / N)
+    float* F = reinterpret_cast<float*>(Tt + (size_t)N * KP);       // [KP][2][64]  g_k C_k, g_k S_k (zero beyond sigma)
+    float* gk = F + (size_t)KP * 128;                               // [KP]
+    float* red = gk + KP;                                           // [16][kDfBins][2][64]
+    float2* tw = reinterpret_cast<float2*>(red);                    // [N]  (cos, sin)(2 pi i / N): only until T is built
     __shared__ int flag;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -188,30 +196,45 @@ spu_dense_fused(const T* __restrict__ x, int N, int D, int64_t row_stride, int s
         sincospi(2.0 * (double)i / (double)N, &sd, &cd);
         tw[i] = make_float2((float)cd, (float)sd);
     }
-    for (int k = tid; k <= sigma; k += 64 * kDfWaves) {
+    for (int k = tid; k < KP; k += 64 * kDfWaves) {
         double w = 1.0;
         if (use_hamming && N > 1) w = 0.54 + 0.46 * cospi(2.0 * (double)k / (double)(N - 1));
         const double pair = (k == 0 || 2 * k == N) ? 1.0 : 2.0;       // +k and -k paired (real-signal form)
-        gk[k] = (float)(pair * w / (double)N);
+        gk[k] = k <= sigma ? (float)(pair * w / (double)N) : 0.f;
     }
     __syncthreads();
+    for (int e = tid; e < N * KP; e += 64 * kDfWaves) {
+        const uint32_t n = (uint32_t)e / (uint32_t)KP, k = (uint32_t)e - n * (uint32_t)KP;
+        Tt[e] = tw[(k * n) % (uint32_t)N];                            // k n < 2^24
+    }
+    __syncthreads();                                                  // tw (inside red) is free from here on
 
     // ---- forward (Eq. 4 on the pass band), mask (Eq. 5-6) with the 1/N of Eq. 7
-    for (int k0 = 0; k0 <= sigma; k0 += kDfBins) {
+    for (int k0 = 0; k0 < KP; k0 += kDfBins) {
         float ac[kDfBins], as[kDfBins];
 #pragma unroll
         for (int j = 0; j < kDfBins; ++j) { ac[j] = 0.f; as[j] = 0.f; }
-#pragma unroll 4
-        for (int n = wave; n < N; n += kDfWaves) {
-            const float xv = live ? tr::load(xb + (int64_t)n * row_stride) : 0.f;
-            int idx = (int)(((int64_t)k0 * n) % N);                  // (k n) mod N, wave-uniform
+        for (int nb = wave; nb < N; nb += kDfWaves * kDfChunk) {      // this wavefront's tokens, kDfChunk loads in flight at a time
+            float xv[kDfChunk];
 #pragma unroll
-            for (int j = 0; j < kDfBins; ++j) {
-                const float2 t = tw[idx];
-                ac[j] = fmaf(xv, t.x, ac[j]);
-                as[j] = fmaf(xv, t.y, as[j]);
-                idx += n;
-                if (idx >= N) idx -= N;
+            for (int i = 0; i < kDfChunk; ++i) {
+                const int n = nb + kDfWaves * i;
+                xv[i] = tr::load(xb + (int64_t)(n < N ? n : 0) * row_stride);      // always a valid address: no branch around the load
+            }
+#pragma unroll
+            for (int i = 0; i < kDfChunk; ++i) {
+                // no branch in this loop (a token past the end adds zeros): the loads above stay together, ahead of all uses
+                const int n = nb + kDfWaves * i;
+                const float xi = (live && n < N) ? xv[i] : 0.f;
+                const float4* tn = reinterpret_cast<const float4*>(Tt + (size_t)(n < N ? n : 0) * KP + k0);
+#pragma unroll
+                for (int j = 0; j < kDfBins / 2; ++j) {
+                    const float4 t = tn[j];                           // bins k0 + 2j, k0 + 2j + 1
+                    ac[2 * j] = fmaf(xi, t.x, ac[2 * j]);
+                    as[2 * j] = fmaf(xi, t.y, as[2 * j]);
+                    ac[2 * j + 1] = fmaf(xi, t.z, ac[2 * j + 1]);
+                    as[2 * j + 1] = fmaf(xi, t.w, as[2 * j + 1]);
+                }
             }
         }
 #pragma unroll
@@ -222,12 +245,10 @@ spu_dense_fused(const T* __restrict__ x, int N, int D, int64_t row_stride, int s
         __syncthreads();
         for (int i = tid; i < kDfBins * 128; i += 64 * kDfWaves) {     // i = (j, cos/sin, lane)
             const int k = k0 + (i >> 7);
-            if (k <= sigma) {
-                float sum = 0.f;
+            float sum = 0.f;
 #pragma unroll
-                for (int w = 0; w < kDfWaves; ++w) sum += red[w * kDfBins * 128 + i];
-                F[k * 128 + (i & 127)] = gk[k] * sum;
-            }
+            for (int w = 0; w < kDfWaves; ++w) sum += red[w * kDfBins * 128 + i];
+            F[k * 128 + (i & 127)] = gk[k] * sum;                      // bins past sigma carry weight zero
         }
         __syncthreads();
     }
@@ -236,21 +257,24 @@ spu_dense_fused(const T* __restrict__ x, int N, int D, int64_t row_stride, int s
     float* pout = partial + ((int64_t)b * n_tiles + tile) * N;
     for (int nb = wave; nb < N; nb += kDfWaves * kDfTok) {
         float acc[kDfTok];
-        int idx[kDfTok], stepn[kDfTok];
 #pragma unroll
-        for (int j = 0; j < kDfTok; ++j) {
-            const int n = nb + kDfWaves * j;
-            acc[j] = 0.f; idx[j] = 0; stepn[j] = n < N ? n : 0;
-        }
-        for (int k = 0; k <= sigma; ++k) {
-            const float c = F[k * 128 + lane], sn = F[k * 128 + 64 + lane];
+        for (int j = 0; j < kDfTok; ++j) acc[j] = 0.f;
+        for (int k0 = 0; k0 < KP; k0 += kDfBins) {
+            float fc[kDfBins], fs[kDfBins];
+#pragma unroll
+            for (int q = 0; q < kDfBins; ++q) { fc[q] = F[(k0 + q) * 128 + lane]; fs[q] = F[(k0 + q) * 128 + 64 + lane]; }
 #pragma unroll
             for (int j = 0; j < kDfTok; ++j) {
-                const float2 t = tw[idx[j]];
-                acc[j] = fmaf(c, t.x, acc[j]);
-                acc[j] = fmaf(sn, t.y, acc[j]);
-                idx[j] += stepn[j];
-                if (idx[j] >= N) idx[j] -= N;
+                const int n = nb + kDfWaves * j;
+                const float4* tn = reinterpret_cast<const float4*>(Tt + (size_t)(n < N ? n : 0) * KP + k0);
+#pragma unroll
+                for (int q = 0; q < kDfBins / 2; ++q) {
+                    const float4 t = tn[q];
+                    acc[j] = fmaf(fc[2 * q], t.x, acc[j]);
+                    acc[j] = fmaf(fs[2 * q], t.y, acc[j]);
+                    acc[j] = fmaf(fc[2 * q + 1], t.z, acc[j]);
+                    acc[j] = fmaf(fs[2 * q + 1], t.w, acc[j]);
+                }
             }
         }
 #pragma unroll

@@ -56,8 +56,8 @@ __device__ __forceinline__ void tile_store(__amdgpu_buffer_rsrc_t r, uint32_t by
 }
 
 // out[n] = sum over `count` rows (row stride N floats) of in[row][n], added in row order in fp64; FIN: square root.
-// Up to kTileGroup rows per trip, all loads of a trip in flight together (a short trip re-reads its last row).
-template <int THREADS, int W, bool FIN>
+// Up to TRIP rows per trip, all loads of a trip in flight together (a short trip re-reads its last row).
+template <int THREADS, int W, bool FIN, int TRIP = kTileGroup>
 __device__ __forceinline__ void tile_rows_sum(const float* in, int count, int N, float* out)
 {
     const __amdgpu_buffer_rsrc_t rin = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(in), 0, count * N * 4, 0x00020000);
@@ -66,14 +66,14 @@ __device__ __forceinline__ void tile_rows_sum(const float* in, int count, int N,
         double e[W];
 #pragma unroll
         for (int c = 0; c < W; ++c) e[c] = 0.0;
-        for (int r0 = 0; r0 < count; r0 += kTileGroup) {
+        for (int r0 = 0; r0 < count; r0 += TRIP) {
             const int left = count - r0;
-            tile_vec<W> p[kTileGroup];
+            tile_vec<W> p[TRIP];
 #pragma unroll
-            for (int r = 0; r < kTileGroup; ++r)
+            for (int r = 0; r < TRIP; ++r)
                 p[r] = tile_load<W>(rin, (uint32_t)(((r0 + (r < left ? r : left - 1)) * N + i) * 4));
 #pragma unroll
-            for (int r = 0; r < kTileGroup; ++r)
+            for (int r = 0; r < TRIP; ++r)
 #pragma unroll
                 for (int c = 0; c < W; ++c) e[c] += r < left ? (double)p[r].v[c] : 0.0;
         }
@@ -103,7 +103,9 @@ __device__ __forceinline__ void tiles_to_scores(float* __restrict__ partial /* [
     const int tid = threadIdx.x;
     const int n_groups = (n_tiles + kTileGroup - 1) / kTileGroup;
     unsigned int* cnt = done + (int64_t)b * (n_groups + 1);
-    if (n_groups > 1) {
+    // scalar accesses (W = 1) leave room for 64 loads in flight per thread: up to 64 tiles are added in one level
+    const bool two_level = n_groups > 1 && !(W == 1 && n_tiles <= 64);
+    if (two_level) {
         const int grp = tile / kTileGroup, t_first = grp * kTileGroup;
         const int t_cnt = n_tiles - t_first < kTileGroup ? n_tiles - t_first : kTileGroup;
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wavefront's stores have been performed
@@ -114,14 +116,16 @@ __device__ __forceinline__ void tiles_to_scores(float* __restrict__ partial /* [
         tile_rows_sum<THREADS, W, false>(partial + ((int64_t)b * n_tiles + t_first) * N, t_cnt, N,
                                          gpartial + ((int64_t)b * n_groups + grp) * N);
     }
-    const int last_cnt = n_groups > 1 ? n_groups : n_tiles;
+    const int last_cnt = two_level ? n_groups : n_tiles;
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();                             // also: every thread has read the flag
     if (tid == 0) *flag = atomicInc(cnt, (unsigned)last_cnt - 1u) == (unsigned)last_cnt - 1u;
     __syncthreads();
     if (!*flag) return;
-    tile_rows_sum<THREADS, W, true>(n_groups > 1 ? gpartial + (int64_t)b * n_groups * N : partial + (int64_t)b * n_tiles * N,
-                                    last_cnt, N, scores + (int64_t)b * N);
+    if (two_level)
+        tile_rows_sum<THREADS, W, true>(gpartial + (int64_t)b * n_groups * N, last_cnt, N, scores + (int64_t)b * N);
+    else
+        tile_rows_sum<THREADS, W, true, (W == 1 ? 64 : kTileGroup)>(partial + (int64_t)b * n_tiles * N, last_cnt, N, scores + (int64_t)b * N);
 }
 
 // Host side: counters for one launch over `samples` samples with `n_tiles` tiles each (device pointer into
