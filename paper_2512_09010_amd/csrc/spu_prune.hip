@@ -154,6 +154,7 @@ spu_gather(const unsigned char* __restrict__ x, const int32_t* __restrict__ kept
 // its share of the kept rows: row q goes to wavefront q mod (4 G) of the sample.  Group 0 also writes
 // kept_idx.  Compared with a selection launch followed by a gather launch this saves a dispatch and the
 // wait between the two, which is most of the time at these sizes.
+typedef unsigned int prune_u32x4 __attribute__((__vector_size__(16)));
 constexpr int kFusedMaxN = 4096, kFusedThreads = 256, kFusedKeys = kFusedMaxN / kFusedThreads;
 
 template <int BYTES>
@@ -255,8 +256,18 @@ spu_prune_fused(const unsigned char* __restrict__ x, const float* __restrict__ s
         const unsigned char* in = x + ((int64_t)b * N + src) * row_bytes_in;
         unsigned char* o = x_out + ((int64_t)b * n_keep + q) * row_bytes_out;
         if (BYTES == 16) {
-            for (int64_t i = (int64_t)lane * 16; i < row_bytes_out; i += 64 * 16)
-                *reinterpret_cast<uint4*>(o + i) = *reinterpret_cast<const uint4*>(in + i);
+            // eight 16-byte pieces per lane in flight before the first store (bounds by the buffer descriptors: pieces
+            // past the end of the row read zeros and write nothing), so a row costs one trip to memory, not seven
+            const int rb = (int)(row_bytes_out > 0x7fffffff ? 0x7fffffff : row_bytes_out);
+            const __amdgpu_buffer_rsrc_t ri = __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned char*>(in), 0, rb, 0x00020000);
+            const __amdgpu_buffer_rsrc_t ro = __builtin_amdgcn_make_buffer_rsrc(o, 0, rb, 0x00020000);
+            for (int base = 0; base < rb; base += 8 * 1024) {
+                prune_u32x4 v[8];
+#pragma unroll
+                for (int k = 0; k < 8; ++k) v[k] = __builtin_amdgcn_raw_buffer_load_b128(ri, base + k * 1024 + lane * 16, 0, 0);
+#pragma unroll
+                for (int k = 0; k < 8; ++k) __builtin_amdgcn_raw_buffer_store_b128(v[k], ro, base + k * 1024 + lane * 16, 0, 0);
+            }
         } else if (BYTES == 4) {
             for (int64_t i = (int64_t)lane * 4; i < row_bytes_out; i += 64 * 4)
                 *reinterpret_cast<uint32_t*>(o + i) = *reinterpret_cast<const uint32_t*>(in + i);
