@@ -622,11 +622,15 @@ struct PairPlan { int segs, seg_out, waves; };
 
 // Cut the nd2 outputs of a line so that a workgroup needs at most `nw` wavefronts: its own rows,
 // two rows below (one more wavefront at most) and the single-row wavefront above.
-PairPlan plan_pair(int L2, int nw)
+PairPlan plan_pair(int L2, int nw, int64_t lines)
 {
     const int nd2 = L2 / 2;
     PairPlan p;
-    static const int forced = getenv("LUVC_OIM_SEG") ? atoi(getenv("LUVC_OIM_SEG")) : 0;   // tuning knob: outputs per workgroup
+    static const int env_forced = getenv("LUVC_OIM_SEG") ? atoi(getenv("LUVC_OIM_SEG")) : 0;   // tuning knob: outputs per workgroup
+    // A grid with fewer line positions than the chip has CUs would leave most of it idle with one workgroup
+    // per position: cut the lines into runs of 8 outputs then (measured on 2 x 112 x 112, 56 x 56 and
+    // 28 x 28 grids: 64 us for the three calls against 78; runs of 2, 6 or 14 gain less).
+    const int forced = env_forced > 0 ? env_forced : ((lines < 256 && nd2 > 8) ? 8 : 0);
     if ((L2 + 3) / 4 <= nw && forced <= 0) {
         p.segs = 1;
         p.seg_out = nd2;
@@ -666,7 +670,7 @@ luvc_status launch_pair(const T* x, const int32_t* sizes_in, int B, int H, int W
     g.n_in = H * W;
     g.n_out = (H / 2) * Wo;
     g.D = D;
-    const PairPlan p = plan_pair(g.L2, NW);
+    const PairPlan p = plan_pair(g.L2, NW, (int64_t)B * g.nd1);
     g.segs = p.segs;
     g.seg_out = p.seg_out;
     const size_t lds = (size_t)p.waves * N * 64 * 4;           // at most 16 * 10 * 256 = 40 KiB
