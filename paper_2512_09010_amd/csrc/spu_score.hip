@@ -295,10 +295,18 @@ static std::atomic<unsigned> g_spu_slot{0};
 
 unsigned int* spu_take_counters()
 {
-    unsigned int* base = nullptr;
-    if (hipGetSymbolAddress((void**)&base, HIP_SYMBOL(g_spu_done)) != hipSuccess) {
-        check_launch("spu score (counters)");
-        return nullptr;
+    // every GPU holds its own copy of the array at its own address: looked up once per device, with that device current
+    constexpr int kMaxDev = 64;
+    static std::atomic<unsigned int*> base_of[kMaxDev];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDev) { set_error("spu score: no current device"); return nullptr; }
+    unsigned int* base = base_of[dev].load(std::memory_order_acquire);
+    if (!base) {
+        if (hipGetSymbolAddress((void**)&base, HIP_SYMBOL(g_spu_done)) != hipSuccess || !base) {
+            check_launch("spu score (counters)");
+            return nullptr;
+        }
+        base_of[dev].store(base, std::memory_order_release);
     }
     return base + (size_t)(g_spu_slot.fetch_add(1) % kSlots) * kSlotCounters;
 }

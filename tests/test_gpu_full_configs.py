@@ -84,3 +84,49 @@ def test_spu_full(oracle, i):
     np.testing.assert_array_equal(kept, oracle.spu_prune(got, w.n_keep)["kept_idx"])   # selection exact on own scores
     np.testing.assert_array_equal(kept, full["kept_idx"])                               # and equal to the oracle's keep set
     np.testing.assert_array_equal(to_host_f64(pr["x"]), full["x"])                      # original tokens, bit copies
+
+
+def test_step_replayed_from_a_hip_graph():
+    """The three calls of a step enqueue kernels only (no allocation, no host synchronisation, no memset), so a step can
+    be captured into a HIP graph; every replay, with eager work and synchronisations in between, must reproduce the
+    eager results bit for bit."""
+    w = wl.mini(1)
+    code = lv.LUVC_BF16
+    xo = to_dev(wl.oim_input(w), w.dtype)
+    xs = to_dev(wl.spu_input(w), w.dtype)
+    passes = w.oim_calls[0]
+    eager_o = lv.luvc_oim_merge(xo, passes)
+    eager_s = lv.luvc_spu_score(xs, w.sigma, True)
+    eager_p = lv.luvc_spu_prune(xs, eager_s, w.n_keep)
+    torch.cuda.synchronize()
+    B, H, W, D = xo.shape
+    Ho, Wo = lv.out_grid(H, W, passes)
+    out = dict(x=torch.empty_like(eager_o["x"]), sizes=torch.empty_like(eager_o["sizes"]),
+               merged_map=torch.empty_like(eager_o["merged_map"]), kept_map=torch.empty_like(eager_o["kept_map"]))
+    ws_o = torch.empty(max(256, lv.luvc_oim_workspace_bytes(B, H, W, D, code, passes)), dtype=torch.uint8, device="cuda")
+    ws_s = torch.empty(max(256, lv.luvc_spu_workspace_bytes(w.spu_B, w.spu_N, w.spu_D, code, w.sigma)), dtype=torch.uint8, device="cuda")
+    scores = torch.empty_like(eager_s)
+    pr = dict(kept_idx=torch.empty_like(eager_p["kept_idx"]), x=torch.empty_like(eager_p["x"]))
+    side = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            st = torch.cuda.current_stream()
+            lv.luvc_oim_merge(xo, passes, workspace=ws_o, stream=st, out=out)
+            lv.luvc_spu_score(xs, w.sigma, True, workspace=ws_s, stream=st, out=scores)
+            lv.luvc_spu_prune(xs, scores, w.n_keep, stream=st, out=pr)
+    torch.cuda.synchronize()
+    for rep in range(4):
+        for t in (out["x"], scores, pr["x"]):
+            t.zero_()
+        out["merged_map"].fill_(-1); pr["kept_idx"].fill_(-1)
+        ws_s.fill_(0xFF)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        lv.luvc_spu_score(xs, w.sigma, True)                                   # eager work between the replays
+        torch.cuda.synchronize()
+        assert torch.equal(out["x"].view(torch.int16), eager_o["x"].view(torch.int16)), rep
+        assert torch.equal(out["merged_map"], eager_o["merged_map"]) and torch.equal(out["kept_map"], eager_o["kept_map"]), rep
+        assert torch.equal(scores.view(torch.int32), eager_s.view(torch.int32)), rep
+        assert torch.equal(pr["kept_idx"], eager_p["kept_idx"]) and torch.equal(pr["x"].view(torch.int16), eager_p["x"].view(torch.int16)), rep
