@@ -233,13 +233,14 @@ def main():
     roofline["calls_ms"] = {n: round(float(v), 5) for n, v in zip(["oim", "spu_score", "spu_prune"], seg_mean)}
 
     result = {
-        "metric": "visual tokens compressed/sec (OIM+SPU)", "value": round(tokens_per_s, 1), "unit": "tokens/s",
+        "metric": "visual tokens compressed/sec (OIM+SPU) on 1 MI355X; % of peak HBM GB/s", "value": round(tokens_per_s, 1), "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "tokens_per_step": w.tokens_in, "oim": f"{w.grids}x{w.H}x{w.W}x{w.D}",
                    "spu": f"{w.spu_B}x{w.spu_N}x{w.spu_D}", "n_keep": w.n_keep, "sigma": w.sigma,
                    "rotating_input_sets": n_rot, "input_gen_s": round(gen_s, 1)},
         "roofline": roofline,
+        "pct_of_peak_hbm": round(100.0 * roofline["whole_step"]["frac"], 2),      # algorithmic bytes of the whole step / step time / 8 TB/s
     }
     if pipelined:
         result["pipelined"] = pipelined
