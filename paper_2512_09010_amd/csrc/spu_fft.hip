@@ -271,10 +271,12 @@ spu_fft16q(const T* __restrict__ x, int N, int D, int64_t row_stride, int sigma,
             tw[n34 + i] = make_float2(sn, -cs);
             if (i) tw[N - i] = make_float2(cs, -sn);
         }
-        if (tid <= sigma) {
+        // the window weights on the upper half of the workgroup: for N <= 1024 the octant above keeps the lower one busy
+        if (tid >= 128 && tid - 128 <= sigma) {
+            const int f = tid - 128;
             double w = 1.0;
-            if (use_hamming) w = 0.54 + 0.46 * cospi(2.0 * (double)tid / (double)(N - 1));
-            gm[tid] = (float)(w / (double)N);
+            if (use_hamming) w = 0.54 + 0.46 * cospi(2.0 * (double)f / (double)(N - 1));
+            gm[f] = (float)(w / (double)N);
         }
     }
     __syncthreads();
