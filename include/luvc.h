@@ -205,6 +205,39 @@ luvc_status luvc_spu_prune(const void* x, const float* scores, int B, int N, int
                            void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * Keep counts of an SPU cascade (Section 3.3, last paragraph; appendix on the SPU parameters l_0, l_delta): SPU is
+ * applied at LLM layers l_0, l_0 + l_delta, ... and removes the visual tokens step by step, all of them at the end.
+ * The paper gives no per-stage counts; this helper applies one keep ratio stage after stage:
+ *   keeps[i] = luvc_keep_count(keeps[i-1], keep_ratio), keeps[-1] = N0; with eliminate != 0 the last stage keeps 0.
+ *   keeps     host [n_stages] int, written
+ * Returns n_stages, or 0 on invalid arguments (N0 < 1, n_stages < 1, keep_ratio outside (0, 1], keeps NULL).
+ * Host arithmetic only.
+ */
+int luvc_spu_cascade_keeps(int N0, double keep_ratio, int n_stages, int eliminate, int* keeps);
+
+/*
+ * One stage of the SPU cascade (Algorithm 2 applied to the tokens that are still alive): luvc_spu_score followed by
+ * luvc_spu_prune on the same x, plus the bookkeeping a cascade needs - where every surviving token sat before the
+ * first stage.
+ *
+ *   x, B, N, D, row_stride, dtype, sigma, use_hamming, scores, workspace   as for luvc_spu_score
+ *                 (workspace of luvc_spu_workspace_bytes(B, N, D, dtype, sigma) bytes)
+ *   n_keep        0..N tokens kept per sample.  0 is the eliminating stage: the call checks B, N, D, launches
+ *                 nothing and writes nothing
+ *   origin_in     device [B,N] int32: position of token n before the first stage, or NULL for the first stage
+ *                 (identity).  Values are copied, never used as addresses
+ *   kept_idx      device [B,n_keep] int32, ascending positions within this stage's x
+ *   origin_out    device [B,n_keep] int32 = origin_in[b, kept_idx[b, q]] (kept_idx itself when origin_in is NULL);
+ *                 feed it to the next stage as origin_in
+ *   x_out         device [B,n_keep,D] dtype (dense): the ORIGINAL rows of the kept tokens, or NULL
+ * Same arithmetic, tie rule, determinism and limits as the two calls it is made of.
+ */
+luvc_status luvc_spu_stage(const void* x, int B, int N, int D, int64_t row_stride, luvc_dtype dtype,
+                           int sigma, int use_hamming, int n_keep, const int32_t* origin_in,
+                           float* scores, int32_t* kept_idx, int32_t* origin_out, void* x_out,
+                           void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * Timing aid for benchmarks (not a step of the paper's method; for callers that want the duration of
  * each kernel the library launches, measured on the launch stream itself).
  *

@@ -195,3 +195,34 @@ def spu_prune(scores, n_keep, x=None):
 
 def keep_count(N, ratio):
     return lib().oracle_keep_count(N, float(ratio))
+
+
+def cascade_keeps(N0, ratio, n_stages, eliminate=True):
+    """Keep counts of an SPU cascade (Section 3.3, last paragraph): the paper removes the visual tokens
+    progressively and entirely at the end but prints no per-stage counts; the reading taken here applies
+    one keep ratio stage after stage, with 0 in the last stage when `eliminate`."""
+    keeps, n = [], int(N0)
+    for i in range(int(n_stages)):
+        n = 0 if (eliminate and i == n_stages - 1) else keep_count(n, ratio)
+        keeps.append(n)
+    return keeps
+
+
+def spu_stage(x, sigma, n_keep, use_hamming=True, origin=None):
+    """One cascade stage: Algorithm 2 on the tokens still alive (x [B,N,D]), and the position each kept
+    token had before the first stage (origin [B,N], identity when None)."""
+    x = _f64(x)
+    B, N, D = x.shape
+    if origin is None:
+        origin = np.tile(np.arange(N, dtype=np.int32), (B, 1))
+    origin = np.asarray(origin)
+    if n_keep == 0:
+        return dict(scores=None, kept_idx=np.empty((B, 0), np.int32), origin=np.empty((B, 0), np.int32),
+                    x=np.empty((B, 0, D), np.float64), margin=float("inf"))
+    scores = spu_score(x, sigma, use_hamming)
+    pr = spu_prune(scores, n_keep, x)
+    org = np.empty((B, n_keep), np.int32)
+    for b in range(B):
+        for q in range(n_keep):
+            org[b, q] = origin[b, pr["kept_idx"][b, q]]
+    return dict(scores=scores, kept_idx=pr["kept_idx"], origin=org, x=pr["x"], margin=pr["margin"])

@@ -19,6 +19,7 @@ LUVC_F32, LUVC_BF16 = 0, 1
 EXPORTS = ("luvc_version", "luvc_last_error", "luvc_oim_plan", "luvc_oim_workspace_bytes", "luvc_oim_merge",
            "luvc_oim_wide_workspace_bytes", "luvc_oim_merge_wide",
            "luvc_oim_keyed_workspace_bytes", "luvc_oim_merge_keyed", "luvc_value_enhance", "luvc_spu_workspace_bytes", "luvc_spu_score", "luvc_keep_count", "luvc_spu_prune",
+           "luvc_spu_cascade_keeps", "luvc_spu_stage",
            "luvc_profile_start", "luvc_profile_stop", "luvc_profile_kernel")
 
 
@@ -72,6 +73,10 @@ def lib() -> ctypes.CDLL:
     L.luvc_keep_count.restype = i
     L.luvc_spu_prune.argtypes = [vp, vp, i, i, i, i64, i, i, vp, vp, vp, sz, vp]
     L.luvc_spu_prune.restype = i
+    L.luvc_spu_cascade_keeps.argtypes = [i, ctypes.c_double, i, i, ctypes.POINTER(ctypes.c_int)]
+    L.luvc_spu_cascade_keeps.restype = i
+    L.luvc_spu_stage.argtypes = [vp, i, i, i, i64, i, i, i, i, vp, vp, vp, vp, vp, vp, sz, vp]
+    L.luvc_spu_stage.restype = i
     L.luvc_profile_start.argtypes = [ctypes.POINTER(vp), i]
     L.luvc_profile_start.restype = i
     L.luvc_profile_stop.argtypes = []
@@ -281,6 +286,40 @@ def luvc_spu_prune(x, scores, n_keep: int, gather: bool = True, stream=None, out
                    x=torch.empty((B, max(n_keep, 0), D), dtype=x.dtype, device=x.device) if (gather and x is not None) else None)
     _check(lib().luvc_spu_prune(xp, _ptr(scores), B, N, D, stride, code, int(n_keep), _ptr(out["kept_idx"]),
                                 _ptr(out.get("x")), None, 0, _stream(stream)))
+    return out
+
+
+def luvc_spu_cascade_keeps(N0: int, keep_ratio: float, n_stages: int, eliminate: bool = True):
+    """Keep counts of the stages of a cascade: one keep ratio stage after stage, 0 at the end when eliminate."""
+    keeps = (ctypes.c_int * max(int(n_stages), 1))()
+    n = lib().luvc_spu_cascade_keeps(int(N0), float(keep_ratio), int(n_stages), int(bool(eliminate)), keeps)
+    if n != n_stages or n_stages < 1:
+        raise LuvcError(LUVC_ERR_INVALID_ARG, "luvc_spu_cascade_keeps rejected its arguments")
+    return [int(k) for k in keeps[:n]]
+
+
+def luvc_spu_stage(x, sigma: int, n_keep: int, use_hamming: bool = True, origin=None, gather: bool = True,
+                   workspace=None, stream=None, out=None):
+    """One cascade stage on x [B,N,D].  Returns dict(scores [B,N] fp32, kept_idx, origin [B,n_keep] int32,
+    x [B,n_keep,D] or None); with n_keep = 0 nothing is launched and the tensors are empty."""
+    import torch
+    assert x.is_cuda and x.dim() == 3 and x.stride(2) == 1 and x.stride(0) == x.shape[1] * x.stride(1)
+    B, N, D = x.shape
+    code = _dtype_code(x)
+    if origin is not None:
+        assert origin.is_cuda and origin.dtype == torch.int32 and origin.is_contiguous() and tuple(origin.shape) == (B, N)
+    k = max(int(n_keep), 0)
+    if workspace is None:
+        need = lib().luvc_spu_workspace_bytes(B, N, D, code, int(sigma)) if k else 0
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=x.device)
+    if out is None:
+        out = dict(scores=torch.empty((B, N), dtype=torch.float32, device=x.device),
+                   kept_idx=torch.empty((B, k), dtype=torch.int32, device=x.device),
+                   origin=torch.empty((B, k), dtype=torch.int32, device=x.device),
+                   x=torch.empty((B, k, D), dtype=x.dtype, device=x.device) if gather else None)
+    _check(lib().luvc_spu_stage(_ptr(x), B, N, D, x.stride(1), code, int(sigma), int(bool(use_hamming)), int(n_keep),
+                                _ptr(origin), _ptr(out["scores"]), _ptr(out["kept_idx"]), _ptr(out["origin"]),
+                                _ptr(out.get("x")), _ptr(workspace), workspace.numel(), _stream(stream)))
     return out
 
 

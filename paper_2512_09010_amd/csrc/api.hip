@@ -480,7 +480,34 @@ luvc_status luvc_spu_prune(const void* x, const float* scores, int B, int N, int
     if (row_stride < D) { set_error("row_stride %lld is smaller than D=%d", (long long)row_stride, D); return LUVC_ERR_INVALID_ARG; }
     if (n_keep < 1 || n_keep > N) { set_error("n_keep=%d must lie in 1..N=%d", n_keep, N); return LUVC_ERR_INVALID_ARG; }
     if ((int64_t)B * N >= ((int64_t)1 << 31)) { set_error("B*N must stay below 2^31"); return LUVC_ERR_UNSUPPORTED; }
-    return spu_prune_run(x, scores, B, N, D, row_stride, dtype, n_keep, kept_idx, x_out, (hipStream_t)hip_stream);
+    return spu_prune_run(x, scores, B, N, D, row_stride, dtype, n_keep, kept_idx, x_out, nullptr, nullptr, (hipStream_t)hip_stream);
+}
+
+int luvc_spu_cascade_keeps(int N0, double keep_ratio, int n_stages, int eliminate, int* keeps)
+{
+    if (N0 < 1 || n_stages < 1 || !keeps || !(keep_ratio > 0.0) || keep_ratio > 1.0) return 0;
+    int n = N0;
+    for (int i = 0; i < n_stages; ++i) {
+        n = (eliminate && i == n_stages - 1) ? 0 : luvc_keep_count(n, keep_ratio);
+        keeps[i] = n;
+    }
+    return n_stages;
+}
+
+luvc_status luvc_spu_stage(const void* x, int B, int N, int D, int64_t row_stride, luvc_dtype dtype, int sigma, int use_hamming,
+                           int n_keep, const int32_t* origin_in, float* scores, int32_t* kept_idx, int32_t* origin_out, void* x_out,
+                           void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    if (n_keep < 0 || n_keep > N) { set_error("n_keep=%d must lie in 0..N=%d", n_keep, N); return LUVC_ERR_INVALID_ARG; }
+    if (n_keep > 0 && (!kept_idx || !origin_out)) { set_error("kept_idx and origin_out must not be NULL"); return LUVC_ERR_INVALID_ARG; }
+    if (n_keep == 0) {                                 // the eliminating stage: nothing survives, nothing is computed or written
+        if (B < 1 || N < 1 || D < 1) { set_error("B, N, D must be positive (got %d,%d,%d)", B, N, D); return LUVC_ERR_INVALID_ARG; }
+        return LUVC_OK;
+    }
+    const luvc_status rc = luvc_spu_score(x, B, N, D, row_stride, dtype, sigma, use_hamming, scores, workspace, workspace_bytes, hip_stream);
+    if (rc != LUVC_OK) return rc;
+    if ((int64_t)B * N >= ((int64_t)1 << 31)) { set_error("B*N must stay below 2^31"); return LUVC_ERR_UNSUPPORTED; }
+    return spu_prune_run(x, scores, B, N, D, row_stride, dtype, n_keep, kept_idx, x_out, origin_in, origin_out, (hipStream_t)hip_stream);
 }
 
 }  // extern "C"

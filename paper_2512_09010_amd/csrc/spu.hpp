@@ -23,6 +23,6 @@ luvc_status spu_score_fft(const void* x, int B, int N, int D, int64_t row_stride
                           float* partial, float* gpartial, int n_tiles, float* scores, hipStream_t st);
 
 luvc_status spu_prune_run(const void* x, const float* scores, int B, int N, int D, int64_t row_stride, luvc_dtype dt,
-                          int n_keep, int32_t* kept_idx, void* x_out, hipStream_t st);
+                          int n_keep, int32_t* kept_idx, void* x_out, const int32_t* origin_in, int32_t* origin_out, hipStream_t st);
 
 }  // namespace luvc

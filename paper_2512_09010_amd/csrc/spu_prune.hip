@@ -48,7 +48,8 @@ __device__ __forceinline__ int block_scan_incl(int v, int* wave_tot /*[16]*/, in
 constexpr int kSelMaxRegKeys = 8;                     // keys cached in registers per thread (N <= 8 * 1024)
 
 __global__ void __launch_bounds__(kSelThreads)
-spu_select(const float* __restrict__ scores, int N, int n_keep, int32_t* __restrict__ kept_idx)
+spu_select(const float* __restrict__ scores, int N, int n_keep, int32_t* __restrict__ kept_idx,
+           const int32_t* __restrict__ origin_in /* [B,N] or null: identity */, int32_t* __restrict__ origin_out /* [B,n_keep] or null */)
 {
     __shared__ int hist[256];
     __shared__ int wave_tot[16];
@@ -116,7 +117,10 @@ spu_select(const float* __restrict__ scores, int N, int n_keep, int32_t* __restr
         const int sel_incl = block_scan_incl(sel ? 1 : 0, wave_tot, &tot_sel);
         if (sel) {
             const int q = sel_before + sel_incl - 1;
-            if (q < n_keep) out[q] = n;
+            if (q < n_keep) {
+                out[q] = n;
+                if (origin_out) origin_out[(int64_t)b * n_keep + q] = origin_in ? origin_in[(int64_t)b * N + n] : n;
+            }
         }
         eq_before += tot_eq;
         sel_before += tot_sel;
@@ -160,7 +164,8 @@ constexpr int kFusedMaxN = 4096, kFusedThreads = 256, kFusedKeys = kFusedMaxN / 
 template <int BYTES>
 __global__ void __launch_bounds__(kFusedThreads)
 spu_prune_fused(const unsigned char* __restrict__ x, const float* __restrict__ scores, int N, int n_keep,
-                int64_t row_bytes_in, int64_t row_bytes_out, int32_t* __restrict__ kept_idx, unsigned char* __restrict__ x_out)
+                int64_t row_bytes_in, int64_t row_bytes_out, int32_t* __restrict__ kept_idx, unsigned char* __restrict__ x_out,
+                const int32_t* __restrict__ origin_in /* [B,N] or null: identity */, int32_t* __restrict__ origin_out /* [B,n_keep] or null */)
 {
     __shared__ uint32_t keys[kFusedMaxN];
     __shared__ int32_t kept[kFusedMaxN];
@@ -247,8 +252,13 @@ spu_prune_fused(const unsigned char* __restrict__ x, const float* __restrict__ s
         }
     }
     __syncthreads();
-    if (g == 0)
+    if (g == 0) {
         for (int q = tid; q < n_keep; q += kFusedThreads) kept_idx[(int64_t)b * n_keep + q] = kept[q];
+        // position of every kept token before the first stage of a cascade
+        if (origin_out)
+            for (int q = tid; q < n_keep; q += kFusedThreads)
+                origin_out[(int64_t)b * n_keep + q] = origin_in ? origin_in[(int64_t)b * N + kept[q]] : kept[q];
+    }
     if (!x_out) return;
     for (int q = g * 4 + wave; q < n_keep; q += G * 4) {
         int src = kept[q];
@@ -279,7 +289,7 @@ spu_prune_fused(const unsigned char* __restrict__ x, const float* __restrict__ s
 }
 
 luvc_status spu_prune_run(const void* x, const float* scores, int B, int N, int D, int64_t row_stride, luvc_dtype dt,
-                          int n_keep, int32_t* kept_idx, void* x_out, hipStream_t st)
+                          int n_keep, int32_t* kept_idx, void* x_out, const int32_t* origin_in, int32_t* origin_out, hipStream_t st)
 {
     const int es = dt == LUVC_F32 ? 4 : 2;
     const int64_t rin = row_stride * es, rout = (int64_t)D * es, rows = (int64_t)B * n_keep;
@@ -289,14 +299,14 @@ luvc_status spu_prune_run(const void* x, const float* scores, int B, int N, int 
         G = G > 256 ? 256 : G;
         const dim3 grid((unsigned)G, (unsigned)B);
         if (v16 || !x_out)
-            LUVC_LAUNCH("spu_prune_fused", (spu_prune_fused<16>), grid, dim3(kFusedThreads), 0, st, (const unsigned char*)x, scores, N, n_keep, rin, rout, kept_idx, (unsigned char*)x_out);
+            LUVC_LAUNCH("spu_prune_fused", (spu_prune_fused<16>), grid, dim3(kFusedThreads), 0, st, (const unsigned char*)x, scores, N, n_keep, rin, rout, kept_idx, (unsigned char*)x_out, origin_in, origin_out);
         else if (es == 4)
-            LUVC_LAUNCH("spu_prune_fused", (spu_prune_fused<4>), grid, dim3(kFusedThreads), 0, st, (const unsigned char*)x, scores, N, n_keep, rin, rout, kept_idx, (unsigned char*)x_out);
+            LUVC_LAUNCH("spu_prune_fused", (spu_prune_fused<4>), grid, dim3(kFusedThreads), 0, st, (const unsigned char*)x, scores, N, n_keep, rin, rout, kept_idx, (unsigned char*)x_out, origin_in, origin_out);
         else
-            LUVC_LAUNCH("spu_prune_fused", (spu_prune_fused<2>), grid, dim3(kFusedThreads), 0, st, (const unsigned char*)x, scores, N, n_keep, rin, rout, kept_idx, (unsigned char*)x_out);
+            LUVC_LAUNCH("spu_prune_fused", (spu_prune_fused<2>), grid, dim3(kFusedThreads), 0, st, (const unsigned char*)x, scores, N, n_keep, rin, rout, kept_idx, (unsigned char*)x_out, origin_in, origin_out);
         return check_launch("spu prune");
     }
-    LUVC_LAUNCH("spu_select", spu_select, dim3((unsigned)B), dim3(kSelThreads), 0, st, scores, N, n_keep, kept_idx);
+    LUVC_LAUNCH("spu_select", spu_select, dim3((unsigned)B), dim3(kSelThreads), 0, st, scores, N, n_keep, kept_idx, origin_in, origin_out);
     if (x_out) {
         const unsigned g = (unsigned)((rows * 64 + 255) / 256);
         if (v16)

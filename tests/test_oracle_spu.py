@@ -192,3 +192,58 @@ def test_end_to_end_energy_ranking(oracle):
     sc = oracle.spu_score(x, 6, True)
     kept = oracle.spu_prune(sc, 9)["kept_idx"][0]
     np.testing.assert_array_equal(kept, np.arange(16, 25))
+
+
+# ---------------------------------------------------------------- cascade (Section 3.3, last paragraph)
+
+def fft_stage(x, sigma, k, origin):
+    """A stage written with the library FFT and a stable argsort: rectangular band, no oracle code."""
+    B, N, D = x.shape
+    F = np.fft.fft(x, axis=1)
+    f = np.minimum(np.arange(N), N - np.arange(N))
+    F[:, f > sigma, :] = 0
+    sc = np.linalg.norm(np.fft.ifft(F, axis=1).real, axis=2)
+    kept = np.stack([stable_topk(sc[b], k) for b in range(B)])
+    return kept, np.take_along_axis(origin, kept, axis=1), np.stack([x[b][kept[b]] for b in range(B)])
+
+
+def test_cascade_keeps_closed_form(oracle):
+    assert oracle.cascade_keeps(1024, 0.5, 4) == [512, 256, 128, 0]
+    assert oracle.cascade_keeps(1024, 0.5, 3, eliminate=False) == [512, 256, 128]
+    assert oracle.cascade_keeps(1024, 0.2, 3) == [205, 41, 0]          # 204.8 -> 205, 41.0 -> 41
+    assert oracle.cascade_keeps(7, 0.01, 3, eliminate=False) == [1, 1, 1]
+    assert oracle.cascade_keeps(9, 1.0, 1) == [0]
+
+
+def test_stage_origin_composes(oracle):
+    # three stages with a "layer" (a fixed mixing of channels plus a per-token drift) between them; the origins of the
+    # survivors must be those of a pipeline written with the library FFT, and must index the first stage's tokens
+    rng = np.random.default_rng(5)
+    B, N, D = 2, 96, 6
+    x0 = rng.standard_normal((B, N, D)) + np.sin(np.arange(N) / 7.0)[None, :, None]
+    mix = rng.standard_normal((D, D)) / np.sqrt(D)
+    keeps, sigmas = [40, 17, 5], [12, 6, 2]
+    x_o, org_o = x0, None
+    x_r, org_r = x0, np.tile(np.arange(N), (B, 1))
+    for k, sg in zip(keeps, sigmas):
+        r = oracle.spu_stage(x_o, sg, k, use_hamming=False, origin=org_o)
+        kept, org_r, xk = fft_stage(x_r, sg, k, org_r)
+        assert r["margin"] > 1e-9
+        np.testing.assert_array_equal(r["kept_idx"], kept)
+        np.testing.assert_array_equal(r["origin"], org_r)
+        np.testing.assert_array_equal(r["x"], xk)
+        assert (np.diff(r["origin"], axis=1) > 0).all()                 # order of the first stage survives
+        x_o, org_o = np.tanh(r["x"] @ mix), r["origin"]
+        x_r = np.tanh(xk @ mix)
+    assert set(org_o[0]) <= set(range(N))
+
+
+def test_stage_identity_origin_and_elimination(oracle):
+    x = rnd((1, 12, 3), 2)
+    r = oracle.spu_stage(x, 3, 5)
+    np.testing.assert_array_equal(r["origin"], r["kept_idx"])
+    perm = np.arange(100, 112, dtype=np.int32)[None, :]
+    r2 = oracle.spu_stage(x, 3, 5, origin=perm)
+    np.testing.assert_array_equal(r2["origin"], r["kept_idx"] + 100)
+    z = oracle.spu_stage(x, 3, 0, origin=perm)
+    assert z["kept_idx"].shape == (1, 0) and z["origin"].shape == (1, 0) and z["x"].shape == (1, 0, 3)
