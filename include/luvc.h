@@ -238,6 +238,62 @@ luvc_status luvc_spu_stage(const void* x, int B, int N, int D, int64_t row_strid
                            void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * Ragged batches (appendix "Iterative Strategy and Pseudocode of OIM": with any-resolution inputs the merges along
+ * the two axes follow the aspect ratio of each image; a batch then holds grids of different shapes).  The items of a
+ * ragged call are packed back to back, item after item, without padding; shapes, schedules and counts are HOST
+ * arrays.  Consecutive items of equal shape and schedule are served by one batched launch sequence, so sort the
+ * batch by shape where the order is free.  Results are those of the batched entry points item by item.  Every item is
+ * checked before the first launch.
+ */
+
+/*
+ * Merge schedule that follows the aspect ratio: every pass halves the longer side of the grid (m = ceil(len/2); a
+ * square grid starts with the row merge of Section 3.2) until H' * W' <= max_tokens.  The paper states that the
+ * number of merges per axis is "adjusted based on the aspect ratio" and prints no rule: this one is this library's.
+ *   passes / n_passes   host, as for luvc_oim_plan; a grid that is within max_tokens already gets the single pass
+ *                       (axis 1, m 0), which copies it, so that n_passes >= 1 always
+ */
+luvc_status luvc_oim_plan_anyres(int H, int W, int64_t max_tokens,
+                                 luvc_oim_pass* passes, int max_passes, int* n_passes);
+
+/*
+ * luvc_oim_merge on n_images grids of their own shape H[i] x W[i] and their own schedule.
+ *   H, W        host [n_images]
+ *   passes      host: the schedules of all images, image after image; n_passes host [n_images], each >= 1
+ *   x           device: image i is a dense [H[i],W[i],D] block at token offset sum_{j<i} H[j]*W[j]
+ *   sizes_in    device, packed like x (one int32 per token), or NULL
+ *   x_out, sizes_out   device, packed by the output grids H'[i] x W'[i] the schedules end at
+ *   merged_map  device, packed like x: input flat index -> output slot WITHIN the image, or NULL
+ *   kept_map    device, packed like x_out: output slot -> input flat index WITHIN the image, or NULL
+ *   workspace   luvc_oim_ragged_workspace_bytes for the same arguments (the largest need of any run)
+ * Limits: those of luvc_oim_merge per run; fewer than 2^31 tokens in the batch.
+ */
+size_t luvc_oim_ragged_workspace_bytes(int n_images, const int32_t* H, const int32_t* W, int D, luvc_dtype dtype,
+                                       const luvc_oim_pass* passes, const int32_t* n_passes);
+luvc_status luvc_oim_merge_ragged(const void* x, const int32_t* sizes_in,
+                                  int n_images, const int32_t* H, const int32_t* W, int D, luvc_dtype dtype,
+                                  const luvc_oim_pass* passes, const int32_t* n_passes,
+                                  void* x_out, int32_t* sizes_out, int32_t* merged_map, int32_t* kept_map,
+                                  void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * luvc_spu_stage on n_samples sequences of their own length.
+ *   N, sigma    host [n_samples]: tokens and cut-off of every sample (0 <= sigma[i] <= N[i]/2)
+ *   n_keep      host [n_samples], each 0..N[i]; NULL = scores only (kept_idx, origin_out, x_out are not touched)
+ *   x           device: sample i is [N[i],*] with row_stride, at token offset sum_{j<i} N[j]
+ *   origin_in   device, packed like x (one int32 per token), or NULL (identity within each sample)
+ *   scores      device fp32, packed like x; written for every sample, also for one that keeps nothing
+ *   kept_idx, origin_out   device int32, packed by n_keep; kept_idx counts from the start of its sample
+ *   x_out       device [sum n_keep, D] dtype, or NULL
+ *   workspace   luvc_spu_ragged_workspace_bytes for the same N, D, dtype, sigma
+ */
+size_t luvc_spu_ragged_workspace_bytes(int n_samples, const int32_t* N, int D, luvc_dtype dtype, const int32_t* sigma);
+luvc_status luvc_spu_stage_ragged(const void* x, int n_samples, const int32_t* N, int D, int64_t row_stride,
+                                  luvc_dtype dtype, const int32_t* sigma, int use_hamming, const int32_t* n_keep,
+                                  const int32_t* origin_in, float* scores, int32_t* kept_idx, int32_t* origin_out,
+                                  void* x_out, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * Timing aid for benchmarks (not a step of the paper's method; for callers that want the duration of
  * each kernel the library launches, measured on the launch stream itself).
  *

@@ -226,3 +226,19 @@ def spu_stage(x, sigma, n_keep, use_hamming=True, origin=None):
         for q in range(n_keep):
             org[b, q] = origin[b, pr["kept_idx"][b, q]]
     return dict(scores=scores, kept_idx=pr["kept_idx"], origin=org, x=pr["x"], margin=pr["margin"])
+
+
+def plan_anyres(H, W, max_tokens):
+    """Aspect-ratio-adaptive schedule (appendix on the iterative strategy of OIM: the merges per axis follow
+    the aspect ratio of the image; no rule is printed).  Reading: while the grid holds more than max_tokens
+    tokens, halve its longer side (the row merge when the sides are equal); a grid that is small enough
+    gets the single pass that merges nothing."""
+    passes = []
+    while H * W > max_tokens:
+        if W >= H:
+            passes.append((1, (W + 1) // 2))
+            W //= 2
+        else:
+            passes.append((0, (H + 1) // 2))
+            H //= 2
+    return passes or [(1, 0)]

@@ -20,6 +20,8 @@ EXPORTS = ("luvc_version", "luvc_last_error", "luvc_oim_plan", "luvc_oim_workspa
            "luvc_oim_wide_workspace_bytes", "luvc_oim_merge_wide",
            "luvc_oim_keyed_workspace_bytes", "luvc_oim_merge_keyed", "luvc_value_enhance", "luvc_spu_workspace_bytes", "luvc_spu_score", "luvc_keep_count", "luvc_spu_prune",
            "luvc_spu_cascade_keeps", "luvc_spu_stage",
+           "luvc_oim_plan_anyres", "luvc_oim_ragged_workspace_bytes", "luvc_oim_merge_ragged",
+           "luvc_spu_ragged_workspace_bytes", "luvc_spu_stage_ragged",
            "luvc_profile_start", "luvc_profile_stop", "luvc_profile_kernel")
 
 
@@ -77,6 +79,17 @@ def lib() -> ctypes.CDLL:
     L.luvc_spu_cascade_keeps.restype = i
     L.luvc_spu_stage.argtypes = [vp, i, i, i, i64, i, i, i, i, vp, vp, vp, vp, vp, vp, sz, vp]
     L.luvc_spu_stage.restype = i
+    ip = ctypes.POINTER(ctypes.c_int32)
+    L.luvc_oim_plan_anyres.argtypes = [i, i, i64, pp, i, ctypes.POINTER(ctypes.c_int)]
+    L.luvc_oim_plan_anyres.restype = i
+    L.luvc_oim_ragged_workspace_bytes.argtypes = [i, ip, ip, i, i, pp, ip]
+    L.luvc_oim_ragged_workspace_bytes.restype = sz
+    L.luvc_oim_merge_ragged.argtypes = [vp, vp, i, ip, ip, i, i, pp, ip, vp, vp, vp, vp, vp, sz, vp]
+    L.luvc_oim_merge_ragged.restype = i
+    L.luvc_spu_ragged_workspace_bytes.argtypes = [i, ip, i, i, ip]
+    L.luvc_spu_ragged_workspace_bytes.restype = sz
+    L.luvc_spu_stage_ragged.argtypes = [vp, i, ip, i, i64, i, ip, i, ip, vp, vp, vp, vp, vp, vp, sz, vp]
+    L.luvc_spu_stage_ragged.restype = i
     L.luvc_profile_start.argtypes = [ctypes.POINTER(vp), i]
     L.luvc_profile_start.restype = i
     L.luvc_profile_stop.argtypes = []
@@ -320,6 +333,77 @@ def luvc_spu_stage(x, sigma: int, n_keep: int, use_hamming: bool = True, origin=
     _check(lib().luvc_spu_stage(_ptr(x), B, N, D, x.stride(1), code, int(sigma), int(bool(use_hamming)), int(n_keep),
                                 _ptr(origin), _ptr(out["scores"]), _ptr(out["kept_idx"]), _ptr(out["origin"]),
                                 _ptr(out.get("x")), _ptr(workspace), workspace.numel(), _stream(stream)))
+    return out
+
+
+def _i32(values):
+    return (ctypes.c_int32 * max(1, len(values)))(*[int(v) for v in values])
+
+
+def luvc_oim_plan_anyres(H: int, W: int, max_tokens: int, max_passes: int = 16) -> List[Tuple[int, int]]:
+    arr = (LuvcPass * max_passes)()
+    n = ctypes.c_int(0)
+    _check(lib().luvc_oim_plan_anyres(H, W, int(max_tokens), arr, max_passes, ctypes.byref(n)))
+    return [(arr[k].axis, arr[k].m) for k in range(n.value)]
+
+
+def luvc_oim_merge_ragged(x, shapes, schedules, sizes=None, want_maps: bool = True, workspace=None, stream=None):
+    """x: CUDA tensor [sum H_i*W_i, D], image after image; shapes [(H_i, W_i)]; schedules: one pass list per image.
+    Returns dict(x [sum H'_i*W'_i, D], sizes, merged_map, kept_map, out_shapes)."""
+    import torch
+    assert x.is_cuda and x.is_contiguous() and x.dim() == 2 and len(shapes) == len(schedules)
+    T, D = x.shape
+    assert T == sum(h * w for h, w in shapes)
+    code = _dtype_code(x)
+    Hs, Ws = _i32([h for h, _ in shapes]), _i32([w for _, w in shapes])
+    flat = [p for sch in schedules for p in sch]
+    parr, nps = _passes(flat), _i32([len(sch) for sch in schedules])
+    out_shapes = [out_grid(h, w, sch) for (h, w), sch in zip(shapes, schedules)]
+    To = sum(max(h, 0) * max(w, 0) for h, w in out_shapes)
+    if workspace is None:
+        need = lib().luvc_oim_ragged_workspace_bytes(len(shapes), Hs, Ws, D, code, parr, nps)
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=x.device)
+    if sizes is not None:
+        assert sizes.is_cuda and sizes.dtype == torch.int32 and sizes.is_contiguous() and sizes.numel() == T
+    out = dict(x=torch.empty((To, D), dtype=x.dtype, device=x.device),
+               sizes=torch.empty((To,), dtype=torch.int32, device=x.device),
+               merged_map=torch.empty((T,), dtype=torch.int32, device=x.device) if want_maps else None,
+               kept_map=torch.empty((To,), dtype=torch.int32, device=x.device) if want_maps else None,
+               out_shapes=out_shapes)
+    _check(lib().luvc_oim_merge_ragged(_ptr(x), _ptr(sizes), len(shapes), Hs, Ws, D, code, parr, nps, _ptr(out["x"]),
+                                       _ptr(out["sizes"]), _ptr(out["merged_map"]), _ptr(out["kept_map"]),
+                                       _ptr(workspace), workspace.numel(), _stream(stream)))
+    return out
+
+
+def luvc_spu_stage_ragged(x, lengths, sigmas, keeps=None, use_hamming: bool = True, origin=None, gather: bool = True,
+                          workspace=None, stream=None):
+    """x: CUDA tensor [sum N_i, D] (rows evenly strided), sample after sample; lengths, sigmas, keeps: per sample.
+    Returns dict(scores [sum N_i] fp32, kept_idx, origin [sum keep_i] int32, x [sum keep_i, D] or None)."""
+    import torch
+    assert x.is_cuda and x.dim() == 2 and x.stride(1) == 1 and len(lengths) == len(sigmas)
+    T, D = x.shape
+    assert T == sum(lengths)
+    code = _dtype_code(x)
+    Ns, Sg = _i32(lengths), _i32(sigmas)
+    Kp = _i32(keeps) if keeps is not None else None
+    K = sum(max(int(k), 0) for k in keeps) if keeps is not None else 0
+    if origin is not None:
+        assert origin.is_cuda and origin.dtype == torch.int32 and origin.is_contiguous() and origin.numel() == T
+    if workspace is None:
+        need = lib().luvc_spu_ragged_workspace_bytes(len(lengths), Ns, D, code, Sg)
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=x.device)
+    out = dict(scores=torch.empty((T,), dtype=torch.float32, device=x.device),
+               kept_idx=torch.empty((K,), dtype=torch.int32, device=x.device),
+               origin=torch.empty((K,), dtype=torch.int32, device=x.device),
+               x=torch.empty((K, D), dtype=x.dtype, device=x.device) if (gather and keeps is not None) else None)
+    # a tensor without elements has no address: hand the library a one-element stand-in it will not touch
+    pad = torch.empty((1,), dtype=torch.int32, device=x.device)
+    ki = out["kept_idx"] if K else pad
+    og = out["origin"] if K else pad
+    _check(lib().luvc_spu_stage_ragged(_ptr(x), len(lengths), Ns, D, x.stride(0), code, Sg, int(bool(use_hamming)), Kp,
+                                       _ptr(origin), _ptr(out["scores"]), _ptr(ki), _ptr(og), _ptr(out["x"]) if K else None,
+                                       _ptr(workspace), workspace.numel(), _stream(stream)))
     return out
 
 

@@ -123,7 +123,7 @@ static OimLayout oim_layout(int B, int D, luvc_dtype dt, const OimPlan& pl, cons
     return L;
 }
 
-static bool workspace_ok(const void* ws, size_t have, size_t need)
+bool workspace_ok(const void* ws, size_t have, size_t need)
 {
     if (need == 0) return true;
     if (!ws) { set_error("workspace is NULL but %zu bytes are needed", need); return false; }

@@ -13,6 +13,8 @@ constexpr int kWave = 64;
 
 // ------------------------------------------------------------------ host-side error text
 void set_error(const char* fmt, ...);
+// true when a workspace of `have` bytes at ws serves a need of `need` bytes (NULL is fine for a need of 0); sets the error text otherwise
+bool workspace_ok(const void* ws, size_t have, size_t need);
 luvc_status check_launch(const char* what);
 
 // ------------------------------------------------------------------ optional timing of the library's launches

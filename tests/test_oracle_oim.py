@@ -342,3 +342,24 @@ def test_value_enhance_closed_forms(oracle):
     np.testing.assert_allclose(A @ out[0], A @ v[0] + (A @ np.log(s[0]))[:, None], rtol=1e-12)
     with pytest.raises(ValueError):
         oracle.value_enhance(v, np.zeros((3, 4), np.int64))
+
+
+def test_plan_anyres_hand_cases(oracle):
+    # wide images are merged along W, tall ones along H, square ones alternate starting with the row merge;
+    # every pass halves (rounding the kept half down), and the plan ends at or below the token budget
+    assert oracle.plan_anyres(64, 64, 1024) == [(1, 32), (0, 32)]
+    assert oracle.plan_anyres(128, 32, 1024) == [(0, 64), (0, 32)]
+    assert oracle.plan_anyres(24, 96, 576) == [(1, 48), (1, 24)]
+    assert oracle.plan_anyres(7, 5, 10) == [(0, 4), (1, 3)]               # 7x5 -> 3x5 -> 3x2
+    assert oracle.plan_anyres(8, 8, 64) == [(1, 0)]
+    for H, W, cap in [(37, 91, 100), (91, 37, 100), (1, 1000, 3), (50, 50, 1)]:
+        h, w = H, W
+        for axis, m in oracle.plan_anyres(H, W, cap):
+            length = w if axis else h
+            assert length == max(h, w) and m == (length + 1) // 2
+            assert h * w > cap
+            if axis:
+                w -= m
+            else:
+                h -= m
+        assert 1 <= h * w <= cap
