@@ -87,11 +87,12 @@ static OimLayout oim_layout(int B, int D, luvc_dtype dt, const OimPlan& pl, cons
 {
     OimLayout L{};
     size_t off = 0;
-    // ping-pong buffers for the outputs of all passes but the last: pass i writes buffer i & 1
+    // ping-pong buffers for the outputs of all launches but the last.  Launch s (one pass, or two passes fused) writes
+    // buffer s & 1; which passes fuse is decided later, so both buffers hold the largest intermediate grid
     size_t tok[2] = {0, 0};
     for (int i = 0; i + 1 < pl.n; ++i) {
         const size_t t = (size_t)B * pl.h[i + 1] * pl.w[i + 1];
-        if (t > tok[i & 1]) tok[i & 1] = t;
+        if (t > tok[0]) tok[0] = tok[1] = t;
     }
     for (int j = 0; j < 2; ++j) {
         L.xbuf[j] = off; off += align_up(tok[j] * D * esize(dt));
@@ -260,9 +261,10 @@ static luvc_status oim_merge_impl(const void* x, const int32_t* sizes_in, int B,
     for (int s = 0; s < n_steps; ++s) {
         const int i = steps[s].first, e = i + steps[s].count - 1;          // passes i..e
         const bool last = e + 1 == pl.n;
-        void* ox = last ? x_out : (void*)(ws + L.xbuf[e & 1]);
-        int32_t* os = last ? sizes_out : (int32_t*)(ws + L.sbuf[e & 1]);
-        int32_t* ok = last ? kept_map : (int32_t*)(ws + L.kbuf[e & 1]);
+        // by launch, not by pass: a fused pair after a single pass would otherwise read and write the same buffer
+        void* ox = last ? x_out : (void*)(ws + L.xbuf[s & 1]);
+        int32_t* os = last ? sizes_out : (int32_t*)(ws + L.sbuf[s & 1]);
+        int32_t* ok = last ? kept_map : (int32_t*)(ws + L.kbuf[s & 1]);
         // a call that is a single launch writes its map straight to the caller
         int32_t* pm = (n_steps == 1 && merged_map) ? merged_map : (int32_t*)(ws + L.maps[i]);
         maps[s] = pm;

@@ -84,6 +84,9 @@ def _halving(H, W, order):
     (1, 16, 12, 72, "HWHW"),
     (1, 16, 16, 72, "WHW"),       # a pair followed by a single pass
     (1, 12, 12, 1024, "WH"),      # four chunks per lane (fp32 at D=1024 is the single-image configuration)
+    (2, 32, 48, 72, "WWHW"),      # a single pass, then a fused pair, then a single pass: intermediates alternate per launch
+    (2, 48, 32, 72, "HHWH"),
+    (1, 32, 32, 64, "WWHHW"),
 ])
 def test_halving_pairs(oracle, dtype, B, H, W, D, order):
     rng = np.random.default_rng(B * 1000 + H * 100 + W * 10 + D + len(order))
