@@ -177,3 +177,31 @@ def test_determinism(oracle):
     for k in ("x", "sizes", "merged_map", "kept_map"):
         assert torch.equal(a[k].view(torch.uint8) if a[k].dtype == torch.bfloat16 else a[k],
                            b[k].view(torch.uint8) if b[k].dtype == torch.bfloat16 else b[k]), k
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_schedules(oracle, seed):
+    """Seeded random grids and schedules (any axis order, m from 0 to a full halving, up to six passes), so that every
+    mix of the single-pass, fused-pair and general launches and every hand-over between them is met."""
+    rng = np.random.default_rng(1000 + seed)
+    dtype = "bf16" if seed % 2 else "f32"
+    B, H, W = int(rng.integers(1, 4)), int(rng.integers(1, 40)), int(rng.integers(1, 40))
+    D = int(rng.choice([8, 24, 33, 64, 72, 136]))
+    passes, h, w = [], H, W
+    for _ in range(int(rng.integers(1, 7))):
+        axis = int(rng.integers(0, 2))
+        length = w if axis else h
+        if length == 1:
+            m = 0
+        else:
+            kind = rng.integers(0, 3)
+            m = (length + 1) // 2 if kind == 0 else int(rng.integers(0, (length + 1) // 2 + 1))
+            m = min(m, length - 1)
+        passes.append((axis, m))
+        if axis:
+            w -= m
+        else:
+            h -= m
+    x = wl.cast_io(wl.smooth_field(rng, B, H, W, D, 2.0) + 0.2 * rng.standard_normal((B, H, W, D)).astype(np.float32), dtype)
+    sizes = rng.integers(1, 4, (B, H, W)) if seed % 3 == 0 else None
+    run_case(oracle, x, dtype, passes, sizes=sizes, tag=f"fuzz{seed}")
