@@ -88,3 +88,26 @@ def test_wide_workload_shapes(oracle, i):
     x = wl.oim_input(w)[:2]
     passes = [(W_AX, 2), (H_AX, 2)] * 3
     run_wide(oracle, x, w.dtype, passes, 0, tag=w.name)
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_wide_random_schedules(oracle, seed):
+    """Seeded random grids, radii (whole line, 2..4) and schedules of up to four passes with any m."""
+    rng = np.random.default_rng(2000 + seed)
+    dtype = "bf16" if seed % 2 else "f32"
+    radius = int(rng.choice([0, 0, 2, 3, 4]))
+    B, H, W = int(rng.integers(1, 3)), int(rng.integers(1, 30)), int(rng.integers(1, 30))
+    D = int(rng.choice([8, 24, 33, 64, 72, 136]))
+    passes, h, w = [], H, W
+    for _ in range(int(rng.integers(1, 5))):
+        axis = int(rng.integers(0, 2))
+        length = w if axis else h
+        m = 0 if length == 1 else min(int(rng.integers(0, (length + 1) // 2 + 1)), length - 1)
+        passes.append((axis, m))
+        if axis:
+            w -= m
+        else:
+            h -= m
+    x = wl.cast_io(wl.smooth_field(rng, B, H, W, D, 2.0) + 0.3 * rng.standard_normal((B, H, W, D)).astype(np.float32), dtype)
+    sizes = rng.integers(1, 4, (B, H, W)) if seed % 3 == 0 else None
+    run_wide(oracle, x, dtype, passes, radius, sizes=sizes, tag=f"fuzz{seed}")

@@ -190,3 +190,36 @@ def test_gather_rows(dtype, D, pad):
     idx = pr["kept_idx"].long()
     want = torch.gather(xd, 1, idx[:, :, None].expand(B, k, D))
     assert torch.equal(pr["x"].view(torch.int16) if dtype == "bf16" else pr["x"], want.contiguous().view(torch.int16) if dtype == "bf16" else want)
+
+
+@pytest.mark.parametrize("seed", range(20))
+def test_score_and_prune_random_shapes(oracle, seed):
+    """Seeded random (B, N, D, sigma, window, row padding, keep count): lengths that the fft factorisations serve and
+    lengths that they do not, bands from DC only to the widest each path takes, channel counts around the tile edges."""
+    rng = np.random.default_rng(500 + seed)
+    dtype = "bf16" if seed % 2 else "f32"
+    B = int(rng.integers(1, 5))
+    kind = seed % 4
+    if kind == 0:
+        N = int(rng.choice([256, 512, 768, 1024, 1280, 1536]))          # 16 x 16 x N2
+    elif kind == 1:
+        N = int(rng.choice([240, 480, 720, 960, 144, 288, 432, 1008]))  # 16 x 15 x N2, 16 x 9 x N2
+    else:
+        N = int(rng.integers(2, 700))
+    D = int(rng.choice([1, 7, 31, 32, 33, 64, 65, 100, 130, 257]))
+    sigma = int(rng.integers(0, N // 2 + 1))
+    if kind < 2 and seed % 3:
+        sigma = int(rng.integers(0, min(N // 2, 70) + 1))                # inside the band the fft path takes
+    ham = bool(rng.integers(0, 2))
+    pad = int(rng.choice([0, 0, 3, 8]))
+    x = wl.cast_io((rng.standard_normal((B, N, D)) + np.cos(np.arange(N) * rng.uniform(0.01, 0.5))[None, :, None]).astype(np.float32), dtype)
+    xd, got, ref = score_case(oracle, x, dtype, sigma, ham, f"fuzz{seed}", stride_pad=pad)
+    k = int(rng.integers(1, N + 1))
+    # selection on the library's own scores: compare with a stable sort of exactly those values
+    pr = lv.luvc_spu_prune(xd, got, k)
+    torch.cuda.synchronize()
+    g = got.cpu().numpy()
+    for b in range(B):
+        want = np.sort(np.argsort(-g[b], kind="stable")[:k])
+        np.testing.assert_array_equal(pr["kept_idx"][b].cpu().numpy(), want)
+        np.testing.assert_array_equal(to_host_f64(pr["x"][b]), to_host_f64(xd[b])[want])
