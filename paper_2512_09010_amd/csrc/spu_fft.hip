@@ -18,6 +18,8 @@
 // threads hold 16 points each for the radix-16 side, all 16 hold Q points each for the other side.
 // The pass-band accumulators F stay in registers across the N2 subsequences, so x is read exactly
 // once and nothing but N floats per tile is written.
+#include <type_traits>
+
 #include "common.hpp"
 #include "spu.hpp"
 #include "spu_tiles.hpp"
@@ -192,7 +194,7 @@ __device__ __forceinline__ float row16_sum(float v)
 #define LUVC_FFT_WAVES 2
 #endif
 template <typename T, int Q, bool POW2, bool ALIGNED>
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(LUVC_FFT_WAVES)))
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((Q == 9 || (Q == 15 && sizeof(T) == 2)) ? 3 : LUVC_FFT_WAVES)))
 spu_fft16q(const T* __restrict__ x, int N, int D, int64_t row_stride, int sigma, int use_hamming,
            float* __restrict__ partial /* [B, n_tiles, N] */, float* __restrict__ gpartial /* [B, n_groups, N] */,
            unsigned int* __restrict__ done /* [B][1 + n_groups], zero between calls */, float* __restrict__ scores /* [B, N] */)
@@ -311,7 +313,9 @@ spu_fft16q(const T* __restrict__ x, int N, int D, int64_t row_stride, int sigma,
     };
 
     // ------------------------------------------------------------------ forward (Eq. 4 on the pass band)
-    for (int n2 = 0; n2 < N2; ++n2) {
+    // The subsequence n2 = 0 carries the twiddle W_N^0 = 1: its pass is a copy of the loop body without the
+    // pass-band multiplications (the same holds for the inverse below).
+    auto forward = [&](int n2, auto first) {
         cf v[16];
 #pragma unroll
         for (int j = 0; j < 16; ++j) v[j] = pio::widen(raw[j]);
@@ -333,10 +337,18 @@ spu_fft16q(const T* __restrict__ x, int N, int D, int64_t row_stride, int sigma,
         dftq<Q, false>::run(u);                  // over the residue -> kb ; u[kb] = Y[t + 16 kb]
 #pragma unroll
         for (int kb = 0; kb < Q; ++kb) {
-            const float2 w = tw_k(kb, n2);
-            F[kb] = F[kb] + cmulc(u[kb], cf{w.x, w.y});    // * W_N^{k n2}
+            if constexpr (decltype(first)::value) {
+                F[kb] = u[kb];
+                ph[kb] = kpos[kb];               // (k * 1) mod N for the next subsequence
+            }
+            else {
+                const float2 w = tw_k(kb, n2);
+                F[kb] = F[kb] + cmulc(u[kb], cf{w.x, w.y});    // * W_N^{k n2}
+            }
         }
-    }
+    };
+    forward(0, std::true_type{});
+    for (int n2 = 1; n2 < N2; ++n2) forward(n2, std::false_type{});
     // ------------------------------------------------------------------ mask (Eq. 5-6) with the 1/N of Eq. 7
 #pragma unroll
     for (int kb = 0; kb < Q; ++kb) {
@@ -347,12 +359,18 @@ spu_fft16q(const T* __restrict__ x, int N, int D, int64_t row_stride, int sigma,
         ph[kb] = 0;
     }
     // ------------------------------------------------------------------ inverse (Eq. 7) and energy (Eq. 8)
-    for (int n2 = 0; n2 < N2; ++n2) {
+    auto inverse = [&](int n2, auto first) {
         cf u[Q];
 #pragma unroll
         for (int kb = 0; kb < Q; ++kb) {
-            const float2 w = tw_k(kb, n2);
-            u[kb] = cmul(F[kb], cf{w.x, w.y});   // F[k] W_N^{-k n2}
+            if constexpr (decltype(first)::value) {
+                u[kb] = F[kb];
+                ph[kb] = kpos[kb];
+            }
+            else {
+                const float2 w = tw_k(kb, n2);
+                u[kb] = cmul(F[kb], cf{w.x, w.y});   // F[k] W_N^{-k n2}
+            }
         }
         dftq<Q, true>::run(u);                   // over kb -> residue s
         o1 = 0;
@@ -377,7 +395,9 @@ spu_fft16q(const T* __restrict__ x, int N, int D, int64_t row_stride, int sigma,
             }
         }
         __syncthreads();
-    }
+    };
+    inverse(0, std::true_type{});
+    for (int n2 = 1; n2 < N2; ++n2) inverse(n2, std::false_type{});
     float* pout = partial + ((int64_t)b * n_tiles + tile) * N;
     for (int n = tid; n < N; n += 256) {         // n = N2 (Q j + t') + n2
         const int n2 = POW2 ? (n & (N2 - 1)) : n % N2;
