@@ -13,8 +13,8 @@ namespace luvc {
 namespace {
 
 struct OimRun {
-    int first, count;            // images first .. first + count - 1
-    int H, W, Ho, Wo;
+    int count;                   // consecutive images of this shape and schedule
+    int H, W;
     const luvc_oim_pass* passes;
     int n_passes;
     int64_t tok_in, tok_out;     // packed token offsets of the first image
@@ -49,7 +49,7 @@ bool oim_runs(int n_images, const int32_t* H, const int32_t* W, const luvc_oim_p
         const bool extend = !runs->empty() && runs->back().H == H[i] && runs->back().W == W[i] &&
                             same_schedule(runs->back().passes, runs->back().n_passes, p, n_passes[i]);
         if (extend) ++runs->back().count;
-        else runs->push_back(OimRun{i, 1, H[i], W[i], h, w, p, n_passes[i], tin, tout});
+        else runs->push_back(OimRun{1, H[i], W[i], p, n_passes[i], tin, tout});
         tin += (int64_t)H[i] * W[i];
         tout += (int64_t)h * w;
         if (tin >= ((int64_t)1 << 31)) { set_error("the packed batch must stay below 2^31 tokens"); return false; }
@@ -59,7 +59,7 @@ bool oim_runs(int n_images, const int32_t* H, const int32_t* W, const luvc_oim_p
 }
 
 struct SpuRun {
-    int first, count, N, sigma, keep;
+    int count, N, sigma, keep;   // consecutive samples with these parameters
     int64_t tok_in, tok_out;
 };
 
@@ -75,7 +75,7 @@ bool spu_runs(int n_samples, const int32_t* N, const int32_t* sigma, const int32
         const bool extend = !runs->empty() && runs->back().N == N[i] && runs->back().sigma == sigma[i] && runs->back().keep == keep &&
                             runs->back().count < 65535;
         if (extend) ++runs->back().count;
-        else runs->push_back(SpuRun{i, 1, N[i], sigma[i], keep, tin, tout});
+        else runs->push_back(SpuRun{1, N[i], sigma[i], keep, tin, tout});
         tin += N[i];
         tout += keep;
         if (tin >= ((int64_t)1 << 31)) { set_error("the packed batch must stay below 2^31 tokens"); return false; }
