@@ -32,6 +32,8 @@ def parse():
     ap.add_argument("--no-pipelined", dest="pipelined", action="store_false", help="skip the two-stream leg")
     ap.add_argument("--oim-wide", action="store_true",
                     help="also time luvc_oim_merge_wide on the workload's grid in the paper's setting (whole-line matching, merge number 2, three operations)")
+    ap.add_argument("--next-rows", action="store_true",
+                    help="also time the calls beyond the hot path: keyed merge, value enhancement, a cascade, ragged batches")
     ap.add_argument("--rotate-mb", type=float, default=600.0, help="distinct input bytes cycled through (defeats cache reuse)")
     return ap.parse_args()
 
@@ -247,6 +249,9 @@ def main():
     if args.oim_wide:
         result["oim_wide"] = oim_wide_leg(lv, torch, w, xs_oim, n_rot, tdt, code, es, stream, args.steps)
 
+    if args.next_rows:
+        result["next_rows"] = next_rows_leg(lv, torch, w, xs_oim, xs_spu, n_rot, tdt, code, es, stream, min(args.steps, 50))
+
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, x_oim_host, x_spu_host)
     print(json.dumps(result))
@@ -300,6 +305,99 @@ def oim_wide_leg(lv, torch, w, xs_oim, n_rot, tdt, code, es, stream, steps):
             "roofline": {"kernel": "oim_line_gram", "bound": "mfma", "dtype": "f64", "achieved": round(flops / (g * 1e-3) / 1e12, 2) if g else None,
                          "peak": 78.6, "unit": "TFLOP/s", "frac": round(flops / (g * 1e-3) / 1e12 / 78.6, 4) if g else None,
                          "algorithmic_flops_per_call": int(flops)}}
+
+
+def _time_call(torch, lv, call, steps):
+    """ms per call (wall clock over `steps` calls on one stream) and the per-kernel averages of 10 more calls."""
+    import numpy as np
+    for i in range(3):
+        call(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        call(i)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    n_prof = 10
+    prof = lv.LaunchProfile(n_prof * 64)
+    prof.start()
+    for i in range(n_prof):
+        call(i)
+    prof.stop()
+    torch.cuda.synchronize()
+    per = {}
+    for name, t in prof.results():
+        per.setdefault(name, []).append(t)
+    prof.close()
+    kernels = {k: {"launches_per_call": len(v) / n_prof, "avg_us": round(float(np.mean(v)) * 1e3, 2)} for k, v in per.items()}
+    return ms, kernels
+
+
+def next_rows_leg(lv, torch, w, xs_oim, xs_spu, n_rot, tdt, code, es, stream, steps):
+    """Timings of the entry points beyond the hot path, on tensors of the workload's shapes: decisions on a key tensor,
+    value enhancement, a three-stage cascade, ragged batches.  Same rotation over input copies as the main step."""
+    dev = xs_oim[0].device
+    res = {}
+    passes = w.oim_calls[0]
+    B, H, W, D = xs_oim[0].shape
+    Ho, Wo = lv.out_grid(H, W, passes)
+
+    # ---- decisions on a key tensor of 128 channels (one attention head's keys), merge applied to tokens and keys
+    Dm = 128
+    keys = [x[..., :Dm].contiguous() for x in xs_oim[:2]]
+    ws = torch.empty(lv.luvc_oim_keyed_workspace_bytes(B, H, W, D, Dm, code, passes, 1), dtype=torch.uint8, device=dev)
+    out = dict(x=torch.empty((B, Ho, Wo, D), dtype=tdt, device=dev), metric=torch.empty((B, Ho, Wo, Dm), dtype=tdt, device=dev),
+               sizes=torch.empty((B, Ho, Wo), dtype=torch.int32, device=dev), merged_map=torch.empty((B, H * W), dtype=torch.int32, device=dev),
+               kept_map=torch.empty((B, Ho * Wo), dtype=torch.int32, device=dev))
+    ms, kern = _time_call(torch, lv, lambda i: lv.luvc_oim_merge_keyed(xs_oim[i % n_rot], keys[i % 2], passes, 1, workspace=ws, stream=stream, out=out), steps)
+    res["oim_keyed"] = {"what": f"luvc_oim_merge_keyed, keys {B}x{H}x{W}x{Dm}, same schedule as the step", "ms_per_call": round(ms, 5), "kernels": kern}
+
+    # ---- V + log s on a tensor of the encoder grid's size
+    sizes = torch.randint(1, 5, (B, H, W), dtype=torch.int32, device=dev)
+    vout = torch.empty_like(xs_oim[0])
+    ms, kern = _time_call(torch, lv, lambda i: lv.luvc_value_enhance(xs_oim[i % n_rot], sizes, stream=stream, out=vout), steps)
+    k_us = kern.get("value_enhance", {}).get("avg_us")
+    by = 2 * xs_oim[0].numel() * es
+    res["value_enhance"] = {"what": f"luvc_value_enhance on {B * H * W} rows x {D}", "ms_per_call": round(ms, 5), "kernels": kern,
+                            "roofline": {"bound": "hbm", "algorithmic_bytes": by, "achieved": round(by / (k_us * 1e-6) / 1e9, 1) if k_us else None,
+                                         "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(by / (k_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4) if k_us else None}}
+
+    # ---- a cascade of three stages without the layers between them: every stage reads the rows the previous one kept
+    Bs, N, Ds = xs_spu[0].shape
+    keeps = lv.luvc_spu_cascade_keeps(N, w.keep_ratio, 3, eliminate=False)
+    alive = [N] + keeps[:-1]
+    sigmas = [max(1, int(w.keep_ratio * n / 2)) if n > 1 else 0 for n in alive]
+    wss = torch.empty(max(lv.luvc_spu_workspace_bytes(Bs, n, Ds, code, sg) for n, sg in zip(alive, sigmas)), dtype=torch.uint8, device=dev)
+    outs = [dict(scores=torch.empty((Bs, n), dtype=torch.float32, device=dev), kept_idx=torch.empty((Bs, k), dtype=torch.int32, device=dev),
+                 origin=torch.empty((Bs, k), dtype=torch.int32, device=dev), x=torch.empty((Bs, k, Ds), dtype=tdt, device=dev))
+            for n, k in zip(alive, keeps)]
+
+    def cascade(i):
+        x, org = xs_spu[i % n_rot], None
+        for st in range(3):
+            o = lv.luvc_spu_stage(x, sigmas[st], keeps[st], True, origin=org, workspace=wss, stream=stream, out=outs[st])
+            x, org = o["x"], o["origin"]
+    ms, kern = _time_call(torch, lv, cascade, steps)
+    res["spu_cascade"] = {"what": f"three luvc_spu_stage calls, tokens {alive} -> keeps {keeps}, sigma {sigmas}", "ms_per_call": round(ms, 5), "kernels": kern}
+
+    # ---- ragged batches: the workload's tokens as grids of three aspect ratios / samples of two lengths
+    shapes = [(H, W)] * max(1, B // 2) + [(H // 2, W * 2)] * max(1, B // 4) + [(H * 2, W // 2)] * max(1, B // 4)
+    schedules = [lv.luvc_oim_plan_anyres(h, ww, Ho * Wo) for h, ww in shapes]
+    T = sum(h * ww for h, ww in shapes)
+    xr = [x.reshape(-1, D)[:T].contiguous() if x.numel() // D >= T else None for x in xs_oim[:2]]
+    if all(a is not None for a in xr):
+        ms, kern = _time_call(torch, lv, lambda i: lv.luvc_oim_merge_ragged(xr[i % 2], shapes, schedules, stream=stream), steps)
+        res["oim_ragged"] = {"what": f"luvc_oim_merge_ragged, {len(shapes)} grids of shapes {sorted(set(shapes))}, any-res plan to {Ho * Wo} tokens each "
+                                     "(the binding allocates the outputs on every call)", "ms_per_call": round(ms, 5), "kernels": kern}
+    lengths = [N] * max(1, Bs // 2) + [N // 2] * (Bs - max(1, Bs // 2)) * 2
+    if sum(lengths) <= Bs * N:
+        xp = [x.reshape(-1, Ds)[:sum(lengths)] for x in xs_spu[:2]]
+        sg = [max(1, int(w.keep_ratio * n / 2)) for n in lengths]
+        kp = [lv.luvc_keep_count(n, w.keep_ratio) for n in lengths]
+        ms, kern = _time_call(torch, lv, lambda i: lv.luvc_spu_stage_ragged(xp[i % 2], lengths, sg, kp, stream=stream), steps)
+        res["spu_ragged"] = {"what": f"luvc_spu_stage_ragged, lengths {lengths} (the binding allocates the outputs on every call)",
+                             "ms_per_call": round(ms, 5), "kernels": kern}
+    return res
 
 
 def cpu_baseline(w, x_oim_host, x_spu_host):

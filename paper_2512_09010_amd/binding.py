@@ -221,6 +221,10 @@ def luvc_oim_merge_wide(x, passes, radius: int, sizes=None, target_tokens: int =
     return out
 
 
+def luvc_oim_keyed_workspace_bytes(B, H, W, D, Dm, dtype_code, passes, radius) -> int:
+    return lib().luvc_oim_keyed_workspace_bytes(B, H, W, D, Dm, dtype_code, _passes(passes), len(passes), int(radius))
+
+
 def luvc_oim_merge_keyed(x, metric, passes, radius: int = 1, sizes=None, target_tokens: int = 0, want_maps: bool = True,
                          want_metric: bool = True, workspace=None, stream=None, out=None):
     """Decisions on metric [B,H,W,Dm], merge applied to x [B,H,W,D].  Returns dict(x, metric, sizes, merged_map, kept_map)."""

@@ -16,6 +16,8 @@
 //                   64-channel tile fit in LDS (small N and sigma, where the launches themselves dominate)
 #include <atomic>
 
+#include <cstdlib>
+
 #include "common.hpp"
 #include "spu.hpp"
 #include "spu_tiles.hpp"
@@ -155,7 +157,7 @@ spu_finish(const float* __restrict__ partial, int N, int n_tiles, int64_t total,
 // LDS table T[n][k] = (cos, sin)(2 pi k n / N), k < KP (the pass band padded to a multiple of kDfBins), so that
 // a token's kDfBins twiddles are three 16-byte reads and no index arithmetic is left in the loops.
 // Forward: the wavefronts split the tokens (n = wave, wave + 16, ...), each accumulates kDfBins bins at a time,
-// the 16 partial sums of a bin meet in LDS and are added in wavefront order into F = g_k (C_k, S_k).  Inverse:
+// the 16 partial sums of a bin meet in LDS (wavefront w + 8 folded into w, then wavefront order) as F = g_k (C_k, S_k).  Inverse:
 // the wavefronts split the tokens again, kDfTok tokens per register block; energies summed over the lanes;
 // tiles summed by the hand-over of spu_tiles.hpp.
 constexpr int kDfWaves = 16, kDfBins = 6, kDfTok = 4, kDfChunk = 16;
@@ -165,8 +167,20 @@ static int dense_fused_kp(int sigma) { return (sigma + 1 + kDfBins - 1) / kDfBin
 static size_t dense_fused_lds(int N, int sigma)
 {
     const size_t kp = (size_t)dense_fused_kp(sigma);
-    const size_t red = sizeof(float) * (size_t)kDfWaves * kDfBins * 128;           // also holds the N-entry table while T is built
+    const size_t red = sizeof(float) * (size_t)(kDfWaves / 2) * kDfBins * 128;     // also holds the N-entry table while T is built
     return sizeof(float2) * (size_t)N * kp + sizeof(float) * (kp * 128 + kp) + (red > sizeof(float2) * (size_t)N ? red : sizeof(float2) * (size_t)N);
+}
+
+// LDS a workgroup of the one-launch kernel may take (of the 160 KB of a compute unit; above 64 KB one workgroup
+// per compute unit is resident).  LUVC_SPU_DENSE_LDS_KB overrides it for measurements.
+static size_t dense_fused_cap()
+{
+    static const size_t cap = [] {
+        const char* e = getenv("LUVC_SPU_DENSE_LDS_KB");
+        const long kb = e ? atol(e) : 144;
+        return (size_t)(kb < 0 ? 0 : kb > 144 ? 144 : kb) * 1024;
+    }();
+    return cap;
 }
 
 template <typename T>
@@ -181,7 +195,7 @@ spu_dense_fused(const T* __restrict__ x, int N, int D, int64_t row_stride, int s
     float2* Tt = dsm;                                               // [N][KP]  (cos, sin)(2 pi k n / N)
     float* F = reinterpret_cast<float*>(Tt + (size_t)N * KP);       // [KP][2][64]  g_k C_k, g_k S_k (zero beyond sigma)
     float* gk = F + (size_t)KP * 128;                               // [KP]
-    float* red = gk + KP;                                           // [16][kDfBins][2][64]
+    float* red = gk + KP;                                           // [8][kDfBins][2][64]
     float2* tw = reinterpret_cast<float2*>(red);                    // [N]  (cos, sin)(2 pi i / N): only until T is built
     __shared__ int flag;
     const int tid = threadIdx.x, lane = tid & 63;
@@ -190,6 +204,19 @@ spu_dense_fused(const T* __restrict__ x, int N, int D, int64_t row_stride, int s
     const int d = tile * 64 + lane;
     const bool live = d < D;
     const T* xb = x + (int64_t)b * N * row_stride + (live ? d : 0);
+
+    // A sample of at most 16 x kDfChunk tokens gives every wavefront a single batch of tokens: it is fetched once, here,
+    // ahead of the table arithmetic, and serves all groups of bins.  Longer samples fetch batch by batch, per group.
+    const bool one_batch = N <= kDfWaves * kDfChunk;
+    auto fetch = [&](int nb, float (&xv)[kDfChunk]) {
+#pragma unroll
+        for (int i = 0; i < kDfChunk; ++i) {
+            const int n = nb + kDfWaves * i;
+            xv[i] = tr::load(xb + (int64_t)(n < N ? n : 0) * row_stride);          // always a valid address: no branch around the load
+        }
+    };
+    float x0[kDfChunk];
+    if (one_batch) fetch(wave, x0);
 
     for (int i = tid; i < N; i += 64 * kDfWaves) {
         double sd, cd;
@@ -214,16 +241,10 @@ spu_dense_fused(const T* __restrict__ x, int N, int D, int64_t row_stride, int s
         float ac[kDfBins], as[kDfBins];
 #pragma unroll
         for (int j = 0; j < kDfBins; ++j) { ac[j] = 0.f; as[j] = 0.f; }
-        for (int nb = wave; nb < N; nb += kDfWaves * kDfChunk) {      // this wavefront's tokens, kDfChunk loads in flight at a time
-            float xv[kDfChunk];
+        auto accumulate = [&](int nb, const float (&xv)[kDfChunk]) {
 #pragma unroll
             for (int i = 0; i < kDfChunk; ++i) {
-                const int n = nb + kDfWaves * i;
-                xv[i] = tr::load(xb + (int64_t)(n < N ? n : 0) * row_stride);      // always a valid address: no branch around the load
-            }
-#pragma unroll
-            for (int i = 0; i < kDfChunk; ++i) {
-                // no branch in this loop (a token past the end adds zeros): the loads above stay together, ahead of all uses
+                // no branch in this loop (a token past the end adds zeros): the loads stay together, ahead of all uses
                 const int n = nb + kDfWaves * i;
                 const float xi = (live && n < N) ? xv[i] : 0.f;
                 const float4* tn = reinterpret_cast<const float4*>(Tt + (size_t)(n < N ? n : 0) * KP + k0);
@@ -236,18 +257,40 @@ spu_dense_fused(const T* __restrict__ x, int N, int D, int64_t row_stride, int s
                     as[2 * j + 1] = fmaf(xi, t.w, as[2 * j + 1]);
                 }
             }
-        }
+        };
+        if (one_batch) accumulate(wave, x0);
+        else
+            for (int nb = wave; nb < N; nb += kDfWaves * kDfChunk) {  // this wavefront's tokens, kDfChunk loads in flight at a time
+                float xv[kDfChunk];
+                fetch(nb, xv);
+                accumulate(nb, xv);
+            }
+        // the 16 partial sums of a bin meet in two steps, so that the exchange buffer holds 8 wavefronts' worth:
+        // wavefront w + 8 hands its sums to wavefront w, then the 8 pair sums are added in wavefront order
+        const int slot = wave & (kDfWaves / 2 - 1);
+        if (wave >= kDfWaves / 2) {
 #pragma unroll
-        for (int j = 0; j < kDfBins; ++j) {
-            red[((wave * kDfBins + j) * 2 + 0) * 64 + lane] = ac[j];
-            red[((wave * kDfBins + j) * 2 + 1) * 64 + lane] = as[j];
+            for (int j = 0; j < kDfBins; ++j) {
+                red[((slot * kDfBins + j) * 2 + 0) * 64 + lane] = ac[j];
+                red[((slot * kDfBins + j) * 2 + 1) * 64 + lane] = as[j];
+            }
+        }
+        __syncthreads();
+        if (wave < kDfWaves / 2) {                                     // reads and rewrites its own slot only
+#pragma unroll
+            for (int j = 0; j < kDfBins; ++j) {
+                float* rc = red + ((slot * kDfBins + j) * 2 + 0) * 64 + lane;
+                float* rs = red + ((slot * kDfBins + j) * 2 + 1) * 64 + lane;
+                *rc = ac[j] + *rc;
+                *rs = as[j] + *rs;
+            }
         }
         __syncthreads();
         for (int i = tid; i < kDfBins * 128; i += 64 * kDfWaves) {     // i = (j, cos/sin, lane)
             const int k = k0 + (i >> 7);
             float sum = 0.f;
 #pragma unroll
-            for (int w = 0; w < kDfWaves; ++w) sum += red[w * kDfBins * 128 + i];
+            for (int w = 0; w < kDfWaves / 2; ++w) sum += red[w * kDfBins * 128 + i];
             F[k * 128 + (i & 127)] = gk[k] * sum;                      // bins past sigma carry weight zero
         }
         __syncthreads();
@@ -343,7 +386,7 @@ luvc_status spu_score_dense(const void* x, int B, int N, int D, int64_t row_stri
     float* Fs = (float*)(ws + L.Fs);
     float* partial = (float*)(ws + L.partial);
     if (L.fast) return spu_score_fft(x, B, N, D, row_stride, dt, sigma, use_hamming, partial, (float*)(ws + L.gpartial), L.n_tiles, scores, st);
-    if (dense_fused_lds(N, sigma) <= 64 * 1024 && spu_tile_groups(L.n_tiles) + 1 <= kSlotCounters) {
+    if (dense_fused_lds(N, sigma) <= dense_fused_cap() && spu_tile_groups(L.n_tiles) + 1 <= kSlotCounters) {
         const int per_launch = kSlotCounters / (spu_tile_groups(L.n_tiles) + 1);
         const size_t es = dt == LUVC_F32 ? 4 : 2;
         for (int b0 = 0; b0 < B; b0 += per_launch) {
