@@ -154,3 +154,46 @@ def test_wide_matching_arguments(L):
     rc = L.luvc_oim_merge_wide(ctypes.c_void_p(256), None, 1, 1, 4096, 64, lv.LUVC_BF16, lv._passes([(1, 2)]), 1, 0, 0,
                                ctypes.c_void_p(256), ctypes.c_void_p(256), None, None, ctypes.c_void_p(256), 1 << 40, None)
     assert rc == lv.LUVC_ERR_UNSUPPORTED                                                  # line longer than the wide path takes
+
+
+def test_anyres_plan_and_cascade_keeps_against_the_oracle(L, oracle):
+    """Host arithmetic of the library against the oracle's separately written routines, over many shapes."""
+    for H in (1, 2, 7, 16, 24, 37, 64, 112, 200):
+        for W in (1, 3, 8, 24, 31, 64, 128, 224):
+            for cap in (1, 10, 64, 144, 1024, 10 ** 6):
+                assert lv.luvc_oim_plan_anyres(H, W, cap) == oracle.plan_anyres(H, W, cap), (H, W, cap)
+    with pytest.raises(lv.LuvcError):
+        lv.luvc_oim_plan_anyres(4, 4, 0)
+    with pytest.raises(lv.LuvcError):
+        lv.luvc_oim_plan_anyres(4096, 4096, 1, max_passes=3)          # needs more passes than the caller has room for
+    for N0 in (1, 8, 196, 1024, 2048):
+        for ratio in (0.05, 0.2, 0.5, 1.0):
+            for stages in (1, 2, 5):
+                for elim in (False, True):
+                    assert lv.luvc_spu_cascade_keeps(N0, ratio, stages, elim) == oracle.cascade_keeps(N0, ratio, stages, elim)
+
+
+def test_ragged_queries_and_arguments(L):
+    """Workspace of a ragged call = the largest need of its runs; bad items are rejected on the host."""
+    i32 = lambda v: (ctypes.c_int32 * len(v))(*v)
+    passes = [(1, 12), (0, 12), (1, 8), (1, 4), (1, 12), (0, 12)]
+    H, W, npz = [24, 16, 24], [24, 16, 24], [2, 2, 2]
+    need = L.luvc_oim_ragged_workspace_bytes(3, i32(H), i32(W), 64, lv.LUVC_BF16, lv._passes(passes), i32(npz))
+    a = lv.luvc_oim_workspace_bytes(1, 24, 24, 64, lv.LUVC_BF16, passes[0:2])
+    b = lv.luvc_oim_workspace_bytes(1, 16, 16, 64, lv.LUVC_BF16, passes[2:4])
+    assert need == max(a, b) > 0
+    # equal neighbours form one run: the need is that of a batch of two
+    need2 = L.luvc_oim_ragged_workspace_bytes(2, i32([24, 24]), i32([24, 24]), 64, lv.LUVC_BF16, lv._passes(passes[0:2] * 2), i32([2, 2]))
+    assert need2 == lv.luvc_oim_workspace_bytes(2, 24, 24, 64, lv.LUVC_BF16, passes[0:2])
+    assert L.luvc_oim_ragged_workspace_bytes(2, i32([24, 0]), i32([24, 24]), 64, lv.LUVC_BF16, lv._passes(passes[0:2] * 2), i32([2, 2])) == 0
+    assert L.luvc_oim_ragged_workspace_bytes(1, i32([4]), i32([4]), 64, lv.LUVC_BF16, lv._passes([(1, 3)]), i32([1])) == 0      # m too large
+    ns, sg = [1024, 1024, 196], [102, 102, 4]
+    need = L.luvc_spu_ragged_workspace_bytes(3, i32(ns), 256, lv.LUVC_BF16, i32(sg))
+    assert need == max(lv.luvc_spu_workspace_bytes(2, 1024, 256, lv.LUVC_BF16, 102), lv.luvc_spu_workspace_bytes(1, 196, 256, lv.LUVC_BF16, 4))
+    assert L.luvc_spu_ragged_workspace_bytes(2, i32([8, 8]), 16, lv.LUVC_BF16, i32([4, 5])) == 0                                # sigma > N/2
+    # a stage call with a bad item is refused before anything is enqueued (no device is touched: pointers are dummies)
+    one = ctypes.c_void_p(256)
+    rc = L.luvc_spu_stage_ragged(one, 2, i32([8, 8]), 16, 16, lv.LUVC_BF16, i32([2, 2]), 1, i32([3, 9]), None, one, one, one, None, None, 0, None)
+    assert rc == lv.LUVC_ERR_INVALID_ARG and b"n_keep" in L.luvc_last_error()
+    rc = L.luvc_oim_merge_ragged(one, None, 1, i32([4]), i32([4]), 16, lv.LUVC_BF16, lv._passes([(2, 1)]), i32([1]), one, one, None, None, None, 0, None)
+    assert rc == lv.LUVC_ERR_INVALID_ARG and b"axis" in L.luvc_last_error()
