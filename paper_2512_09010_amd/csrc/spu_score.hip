@@ -17,6 +17,7 @@
 #include <atomic>
 
 #include <cstdlib>
+#include <type_traits>
 
 #include "common.hpp"
 #include "spu.hpp"
@@ -153,13 +154,14 @@ spu_finish(const float* __restrict__ partial, int N, int n_tiles, int64_t total,
 }
 
 // ------------------------------------------------------------------ one launch for small samples
-// Workgroup (tile, b): 64 channels (lanes) x 16 wavefronts.  The twiddles of every (token, bin) pair sit in an
-// LDS table T[n][k] = (cos, sin)(2 pi k n / N), k < KP (the pass band padded to a multiple of kDfBins), so that
-// a token's kDfBins twiddles are three 16-byte reads and no index arithmetic is left in the loops.
-// Forward: the wavefronts split the tokens (n = wave, wave + 16, ...), each accumulates kDfBins bins at a time,
-// the 16 partial sums of a bin meet in LDS (wavefront w + 8 folded into w, then wavefront order) as F = g_k (C_k, S_k).  Inverse:
-// the wavefronts split the tokens again, kDfTok tokens per register block; energies summed over the lanes;
-// tiles summed by the hand-over of spu_tiles.hpp.
+// Workgroup (tile, b): 64 channels (lanes) x 16 wavefronts.  Tokens are taken in mirrored pairs (p, N - p), which
+// share their cosines and have opposite sines (half the products both ways, half the table).  The twiddles of every
+// (pair, bin) sit in an LDS table T[p][k] = (cos, sin)(2 pi k p / N), p <= N/2, k < KP (the pass band padded to a
+// multiple of kDfBins), so that a pair's kDfBins twiddles are three 16-byte reads and no index arithmetic is left
+// in the loops.  Forward: the wavefronts split the pairs (p = wave, wave + 16, ...), each accumulates kDfBins bins
+// at a time, the 16 partial sums of a bin meet in LDS (wavefront w + 8 folded into w, then wavefront order) as
+// F = g_k (C_k, S_k).  Inverse: the wavefronts split the pairs again, kDfTok pairs per register block; energies
+// summed over the lanes; tiles summed by the hand-over of spu_tiles.hpp.
 constexpr int kDfWaves = 16, kDfBins = 6, kDfTok = 4, kDfChunk = 16;
 
 static int dense_fused_kp(int sigma) { return (sigma + 1 + kDfBins - 1) / kDfBins * kDfBins; }
@@ -168,7 +170,7 @@ static size_t dense_fused_lds(int N, int sigma)
 {
     const size_t kp = (size_t)dense_fused_kp(sigma);
     const size_t red = sizeof(float) * (size_t)(kDfWaves / 2) * kDfBins * 128;     // also holds the N-entry table while T is built
-    return sizeof(float2) * (size_t)N * kp + sizeof(float) * (kp * 128 + kp) + (red > sizeof(float2) * (size_t)N ? red : sizeof(float2) * (size_t)N);
+    return sizeof(float2) * (size_t)(N / 2 + 1) * kp + sizeof(float) * (kp * 128 + kp) + (red > sizeof(float2) * (size_t)N ? red : sizeof(float2) * (size_t)N);
 }
 
 // LDS a workgroup of the one-launch kernel may take (of the 160 KB of a compute unit; above 64 KB one workgroup
@@ -192,8 +194,9 @@ spu_dense_fused(const T* __restrict__ x, int N, int D, int64_t row_stride, int s
     using tr = io_traits<T>;
     extern __shared__ __align__(16) float2 dsm[];
     const int KP = (sigma + 1 + kDfBins - 1) / kDfBins * kDfBins;
-    float2* Tt = dsm;                                               // [N][KP]  (cos, sin)(2 pi k n / N)
-    float* F = reinterpret_cast<float*>(Tt + (size_t)N * KP);       // [KP][2][64]  g_k C_k, g_k S_k (zero beyond sigma)
+    const int P = N / 2 + 1;                                        // token pairs (p, N - p); p = 0 and p = N/2 stand alone
+    float2* Tt = dsm;                                               // [P][KP]  (cos, sin)(2 pi k p / N)
+    float* F = reinterpret_cast<float*>(Tt + (size_t)P * KP);       // [KP][2][64]  g_k C_k, g_k S_k (zero beyond sigma)
     float* gk = F + (size_t)KP * 128;                               // [KP]
     float* red = gk + KP;                                           // [8][kDfBins][2][64]
     float2* tw = reinterpret_cast<float2*>(red);                    // [N]  (cos, sin)(2 pi i / N): only until T is built
@@ -205,18 +208,40 @@ spu_dense_fused(const T* __restrict__ x, int N, int D, int64_t row_stride, int s
     const bool live = d < D;
     const T* xb = x + (int64_t)b * N * row_stride + (live ? d : 0);
 
-    // A sample of at most 16 x kDfChunk tokens gives every wavefront a single batch of tokens: it is fetched once, here,
-    // ahead of the table arithmetic, and serves all groups of bins.  Longer samples fetch batch by batch, per group.
-    const bool one_batch = N <= kDfWaves * kDfChunk;
-    auto fetch = [&](int nb, float (&xv)[kDfChunk]) {
+    // Tokens p and N - p see the same cosines and opposite sines: with u = x[p] + x[N-p], v = x[p] - x[N-p] a bin takes
+    // C += u cos, S += v sin (half the products), and the inverse gives x'[p] = A + B, x'[N-p] = A - B from
+    // A = sum F_c cos, B = sum F_s sin.  A token that stands alone (p = 0, p = N/2) has sin = 0 exactly and a partner
+    // value of zero.
+    // A sample of at most 16 x kDfChunk pairs gives every wavefront a single batch: it is fetched once, here, ahead of
+    // the table arithmetic, and serves all groups of bins.  Longer samples fetch batch by batch, per group.
+    const bool one_batch = P <= kDfWaves * kDfChunk;
+    // (slots = pairs a wavefront takes per batch: half a batch when the whole sample fits in that)
+    auto fetch = [&](int pb, float (&xu)[kDfChunk], float (&xv)[kDfChunk], auto slots) {
+        constexpr int CH = decltype(slots)::value;
+        float xa[CH], xm[CH];
 #pragma unroll
-        for (int i = 0; i < kDfChunk; ++i) {
-            const int n = nb + kDfWaves * i;
-            xv[i] = tr::load(xb + (int64_t)(n < N ? n : 0) * row_stride);          // always a valid address: no branch around the load
+        for (int i = 0; i < CH; ++i) {
+            const int p = pb + kDfWaves * i, q = (p < P && p > 0) ? N - p : 0;     // always valid addresses: no branch around the loads
+            xa[i] = tr::load(xb + (int64_t)(p < P ? p : 0) * row_stride);
+            xm[i] = tr::load(xb + (int64_t)q * row_stride);
+        }
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            const int p = pb + kDfWaves * i;
+            const bool there = live && p < P, paired = there && p > 0 && 2 * p != N;
+            const float a = there ? xa[i] : 0.f, m = paired ? xm[i] : 0.f;
+            xu[i] = a + m;
+            xv[i] = a - m;
         }
     };
-    float x0[kDfChunk];
-    if (one_batch) fetch(wave, x0);
+    using full_t = std::integral_constant<int, kDfChunk>;
+    using half_t = std::integral_constant<int, kDfChunk / 2>;
+    using quarter_t = std::integral_constant<int, kDfChunk / 4>;
+    const bool half_batch = P <= kDfWaves * (kDfChunk / 2), quarter_batch = P <= kDfWaves * (kDfChunk / 4);
+    float u0[kDfChunk], v0[kDfChunk];
+    if (quarter_batch) fetch(wave, u0, v0, quarter_t{});
+    else if (half_batch) fetch(wave, u0, v0, half_t{});
+    else if (one_batch) fetch(wave, u0, v0, full_t{});
 
     for (int i = tid; i < N; i += 64 * kDfWaves) {
         double sd, cd;
@@ -230,7 +255,7 @@ spu_dense_fused(const T* __restrict__ x, int N, int D, int64_t row_stride, int s
         gk[k] = k <= sigma ? (float)(pair * w / (double)N) : 0.f;
     }
     __syncthreads();
-    for (int e = tid; e < N * KP; e += 64 * kDfWaves) {
+    for (int e = tid; e < P * KP; e += 64 * kDfWaves) {
         const uint32_t n = (uint32_t)e / (uint32_t)KP, k = (uint32_t)e - n * (uint32_t)KP;
         Tt[e] = tw[(k * n) % (uint32_t)N];                            // k n < 2^24
     }
@@ -241,29 +266,30 @@ spu_dense_fused(const T* __restrict__ x, int N, int D, int64_t row_stride, int s
         float ac[kDfBins], as[kDfBins];
 #pragma unroll
         for (int j = 0; j < kDfBins; ++j) { ac[j] = 0.f; as[j] = 0.f; }
-        auto accumulate = [&](int nb, const float (&xv)[kDfChunk]) {
+        auto accumulate = [&](int pb, const float (&xu)[kDfChunk], const float (&xv)[kDfChunk], auto slots) {
 #pragma unroll
-            for (int i = 0; i < kDfChunk; ++i) {
-                // no branch in this loop (a token past the end adds zeros): the loads stay together, ahead of all uses
-                const int n = nb + kDfWaves * i;
-                const float xi = (live && n < N) ? xv[i] : 0.f;
-                const float4* tn = reinterpret_cast<const float4*>(Tt + (size_t)(n < N ? n : 0) * KP + k0);
+            for (int i = 0; i < decltype(slots)::value; ++i) {
+                // no branch in this loop (a pair past the end adds zeros): the loads stay together, ahead of all uses
+                const int p = pb + kDfWaves * i;
+                const float4* tn = reinterpret_cast<const float4*>(Tt + (size_t)(p < P ? p : 0) * KP + k0);
 #pragma unroll
                 for (int j = 0; j < kDfBins / 2; ++j) {
                     const float4 t = tn[j];                           // bins k0 + 2j, k0 + 2j + 1
-                    ac[2 * j] = fmaf(xi, t.x, ac[2 * j]);
-                    as[2 * j] = fmaf(xi, t.y, as[2 * j]);
-                    ac[2 * j + 1] = fmaf(xi, t.z, ac[2 * j + 1]);
-                    as[2 * j + 1] = fmaf(xi, t.w, as[2 * j + 1]);
+                    ac[2 * j] = fmaf(xu[i], t.x, ac[2 * j]);
+                    as[2 * j] = fmaf(xv[i], t.y, as[2 * j]);
+                    ac[2 * j + 1] = fmaf(xu[i], t.z, ac[2 * j + 1]);
+                    as[2 * j + 1] = fmaf(xv[i], t.w, as[2 * j + 1]);
                 }
             }
         };
-        if (one_batch) accumulate(wave, x0);
+        if (quarter_batch) accumulate(wave, u0, v0, quarter_t{});
+        else if (half_batch) accumulate(wave, u0, v0, half_t{});
+        else if (one_batch) accumulate(wave, u0, v0, full_t{});
         else
-            for (int nb = wave; nb < N; nb += kDfWaves * kDfChunk) {  // this wavefront's tokens, kDfChunk loads in flight at a time
-                float xv[kDfChunk];
-                fetch(nb, xv);
-                accumulate(nb, xv);
+            for (int pb = wave; pb < P; pb += kDfWaves * kDfChunk) {  // this wavefront's pairs, 2 kDfChunk loads in flight at a time
+                float xu[kDfChunk], xv[kDfChunk];
+                fetch(pb, xu, xv, full_t{});
+                accumulate(pb, xu, xv, full_t{});
             }
         // the 16 partial sums of a bin meet in two steps, so that the exchange buffer holds 8 wavefronts' worth:
         // wavefront w + 8 hands its sums to wavefront w, then the 8 pair sums are added in wavefront order
@@ -298,33 +324,37 @@ spu_dense_fused(const T* __restrict__ x, int N, int D, int64_t row_stride, int s
 
     // ---- inverse (Eq. 7, +k and -k paired) and energy over the tile's channels (Eq. 8)
     float* pout = partial + ((int64_t)b * n_tiles + tile) * N;
-    for (int nb = wave; nb < N; nb += kDfWaves * kDfTok) {
-        float acc[kDfTok];
+    for (int pb = wave; pb < P; pb += kDfWaves * kDfTok) {
+        float accA[kDfTok], accB[kDfTok];
 #pragma unroll
-        for (int j = 0; j < kDfTok; ++j) acc[j] = 0.f;
+        for (int j = 0; j < kDfTok; ++j) { accA[j] = 0.f; accB[j] = 0.f; }
         for (int k0 = 0; k0 < KP; k0 += kDfBins) {
             float fc[kDfBins], fs[kDfBins];
 #pragma unroll
             for (int q = 0; q < kDfBins; ++q) { fc[q] = F[(k0 + q) * 128 + lane]; fs[q] = F[(k0 + q) * 128 + 64 + lane]; }
 #pragma unroll
             for (int j = 0; j < kDfTok; ++j) {
-                const int n = nb + kDfWaves * j;
-                const float4* tn = reinterpret_cast<const float4*>(Tt + (size_t)(n < N ? n : 0) * KP + k0);
+                const int p = pb + kDfWaves * j;
+                const float4* tn = reinterpret_cast<const float4*>(Tt + (size_t)(p < P ? p : 0) * KP + k0);
 #pragma unroll
                 for (int q = 0; q < kDfBins / 2; ++q) {
                     const float4 t = tn[q];
-                    acc[j] = fmaf(fc[2 * q], t.x, acc[j]);
-                    acc[j] = fmaf(fs[2 * q], t.y, acc[j]);
-                    acc[j] = fmaf(fc[2 * q + 1], t.z, acc[j]);
-                    acc[j] = fmaf(fs[2 * q + 1], t.w, acc[j]);
+                    accA[j] = fmaf(fc[2 * q], t.x, accA[j]);
+                    accB[j] = fmaf(fs[2 * q], t.y, accB[j]);
+                    accA[j] = fmaf(fc[2 * q + 1], t.z, accA[j]);
+                    accB[j] = fmaf(fs[2 * q + 1], t.w, accB[j]);
                 }
             }
         }
 #pragma unroll
         for (int j = 0; j < kDfTok; ++j) {
-            const int n = nb + kDfWaves * j;
-            const float e = wave_sum(acc[j] * acc[j]);
-            if (lane == 0 && n < N) tile_store(pout + n, e);
+            const int p = pb + kDfWaves * j;
+            const float xp = accA[j] + accB[j], xq = accA[j] - accB[j];            // x'[p], x'[N - p]
+            const float ep = wave_sum(xp * xp), eq = wave_sum(xq * xq);
+            if (lane == 0 && p < P) {
+                tile_store(pout + p, ep);
+                if (p > 0 && 2 * p != N) tile_store(pout + (N - p), eq);
+            }
         }
     }
     tiles_to_scores<64 * kDfWaves, 1>(partial, gpartial, done, scores, b, tile, n_tiles, N, &flag);
