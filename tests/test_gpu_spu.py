@@ -40,6 +40,8 @@ def score_case(oracle, x_io, dtype, sigma, ham=True, tag="", stride_pad=0):
     (1, 1280, 31, 64),
     (2, 240, 64, 119), (1, 240, 33, 0), (2, 720, 70, 54), (1, 480, 40, 60), (1, 1200, 34, 100),      # Q = 15
     (2, 144, 64, 71), (1, 144, 200, 18), (1, 288, 37, 30), (1, 432, 64, 72), (1, 1008, 32, 7),       # Q = 9
+    # one-launch direct path beyond a single batch of token pairs per wavefront, odd and even lengths, up to its LDS limit
+    (2, 600, 70, 3), (1, 601, 33, 5), (1, 1500, 33, 2), (1, 3000, 64, 1), (1, 4000, 40, 1), (1, 513, 64, 11),
 ])
 def test_score_small_random(oracle, dtype, B, N, D, sigma):
     rng = np.random.default_rng(N * 31 + D)
