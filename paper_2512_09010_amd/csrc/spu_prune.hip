@@ -19,18 +19,26 @@ __device__ __forceinline__ uint32_t score_key(float s)
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
+// inclusive prefix sum over the 64 lanes without the LDS crossbar: shifts inside each row of 16 lanes, then the
+// last lane of rows 0 / 2 into rows 1 / 3, then lane 31 into the upper half (lanes without a source add zero)
+__device__ __forceinline__ uint32_t wave_scan_incl(uint32_t v)
+{
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xf, 0xf, false);     // row_shr:1
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xf, 0xf, false);     // row_shr:2
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xf, 0xf, false);     // row_shr:4
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xf, 0xf, false);     // row_shr:8
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xa, 0xf, false);     // row_bcast:15 -> rows 1, 3
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xc, 0xf, false);     // row_bcast:31 -> rows 2, 3
+    return v;
+}
+
 constexpr int kSelThreads = 1024;
 
 // inclusive block scan of one int per thread; returns the inclusive prefix, *total gets the block sum
 __device__ __forceinline__ int block_scan_incl(int v, int* wave_tot /*[16]*/, int* total)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    int s = v;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        const int t = __shfl_up(s, o, kWave);
-        if (lane >= o) s += t;
-    }
+    const int s = (int)wave_scan_incl((uint32_t)v);
     __syncthreads();                                   // wave_tot may still be read from a previous scan
     if (lane == 63) wave_tot[wave] = s;
     __syncthreads();
@@ -177,7 +185,7 @@ spu_prune_fused(const unsigned char* __restrict__ x, const float* __restrict__ s
 {
     __shared__ uint32_t keys[kFusedMaxN];
     __shared__ int32_t kept[kFusedMaxN];
-    __shared__ int hist[256];
+    __shared__ int hist[4][256];                       // one histogram per digit pass: none has to be cleared in between
     __shared__ uint32_t wave_tot[4];
     __shared__ uint32_t sh_prefix;
     __shared__ int sh_remaining;
@@ -185,7 +193,7 @@ spu_prune_fused(const unsigned char* __restrict__ x, const float* __restrict__ s
     const int g = blockIdx.x, G = gridDim.x, b = blockIdx.y;
     const float* s = scores + (int64_t)b * N;
     for (int n = tid; n < N; n += kFusedThreads) keys[n] = score_key(s[n]);
-    hist[tid] = 0;
+    hist[0][tid] = 0; hist[1][tid] = 0; hist[2][tid] = 0; hist[3][tid] = 0;
     __syncthreads();
     // thread tid owns the K consecutive tokens tid * K .. tid * K + K - 1
     const int K = (N + kFusedThreads - 1) / kFusedThreads, n0 = tid * K;
@@ -195,22 +203,18 @@ spu_prune_fused(const unsigned char* __restrict__ x, const float* __restrict__ s
 
     uint32_t prefix = 0, mask = 0;
     int remaining = n_keep;                            // still to pick among keys matching the prefix
-    for (int shift = 24; shift >= 0; shift -= 8) {
+    for (int shift = 24, pass = 0; shift >= 0; shift -= 8, ++pass) {
+        int* h_pass = hist[pass];
 #pragma unroll
         for (int i = 0; i < kFusedKeys; ++i)
-            if (i < K && n0 + i < N && (key[i] & mask) == prefix) atomicAdd(&hist[(key[i] >> shift) & 255u], 1);
+            if (i < K && n0 + i < N && (key[i] & mask) == prefix) atomicAdd(&h_pass[(key[i] >> shift) & 255u], 1);
         __syncthreads();
         if (wave == 0) {
             // lane l looks at digits 255 - 4 l .. 252 - 4 l, largest first
             int h[4], sum = 0;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) { h[j] = hist[255 - 4 * lane - j]; sum += h[j]; }
-            int incl = sum;
-#pragma unroll
-            for (int o = 1; o < 64; o <<= 1) {
-                const int t = __shfl_up(incl, o, kWave);
-                if (lane >= o) incl += t;
-            }
+            for (int j = 0; j < 4; ++j) { h[j] = h_pass[255 - 4 * lane - j]; sum += h[j]; }
+            const int incl = (int)wave_scan_incl((uint32_t)sum);
             int above = incl - sum;                    // tokens with a larger digit
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
@@ -225,8 +229,6 @@ spu_prune_fused(const unsigned char* __restrict__ x, const float* __restrict__ s
         prefix = sh_prefix;
         remaining = sh_remaining;
         mask |= 255u << shift;
-        hist[tid] = 0;                                 // every wave has passed the barrier after the read above
-        __syncthreads();
     }
     const uint32_t T = prefix;                         // key of the n_keep-th largest score
     const int take_eq = remaining;                     // tokens with key == T that are kept (lowest indices)
@@ -236,12 +238,7 @@ spu_prune_fused(const unsigned char* __restrict__ x, const float* __restrict__ s
 #pragma unroll
     for (int i = 0; i < kFusedKeys; ++i)
         if (i < K && n0 + i < N) cnt += (key[i] > T ? 1u : 0u) + (key[i] == T ? 0x10000u : 0u);
-    uint32_t incl = cnt;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        const uint32_t t = __shfl_up(incl, o, kWave);
-        if (lane >= o) incl += t;
-    }
+    const uint32_t incl = wave_scan_incl(cnt);
     if (lane == 63) wave_tot[wave] = incl;
     __syncthreads();
     uint32_t before = incl - cnt;
