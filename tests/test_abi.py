@@ -197,3 +197,19 @@ def test_ragged_queries_and_arguments(L):
     assert rc == lv.LUVC_ERR_INVALID_ARG and b"n_keep" in L.luvc_last_error()
     rc = L.luvc_oim_merge_ragged(one, None, 1, i32([4]), i32([4]), 16, lv.LUVC_BF16, lv._passes([(2, 1)]), i32([1]), one, one, None, None, None, 0, None)
     assert rc == lv.LUVC_ERR_INVALID_ARG and b"axis" in L.luvc_last_error()
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/luvc.h must be usable from C (and C++) without any HIP or torch header."""
+    import shutil
+    import subprocess
+    src = tmp_path / "use_luvc.c"
+    src.write_text('#include "luvc.h"\nint main(void) { luvc_oim_pass p = {1, 2}; luvc_status (*f)(int, int, int64_t, luvc_oim_pass*, int, int*) = luvc_oim_plan; return (int)sizeof(p) - 8 + (f ? 0 : 1); }\n')
+    inc = os.path.join(ROOT, "include")
+    for cc, std in (("gcc", "-std=c99"), ("g++", "-std=c++11")):
+        if shutil.which(cc) is None:
+            pytest.skip(f"{cc} not installed")
+        args = [cc, std, "-Wall", "-Werror", "-pedantic", "-fsyntax-only", "-I", inc]
+        args += ["-x", "c++", str(src)] if cc == "g++" else [str(src)]
+        r = subprocess.run(args, capture_output=True, text=True)
+        assert r.returncode == 0, r.stderr
