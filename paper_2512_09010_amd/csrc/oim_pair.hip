@@ -332,6 +332,9 @@ template <typename T> __device__ __forceinline__ uint32_t pack_word(double q0, d
 // (2^-126), where it rounds the 8-bit value once more onto the subnormal grid.
 template <> __device__ __forceinline__ uint32_t pack_word<bf16_t>(double q0, double q1)
 {
+    // The three operations must each round on their own: fused into c * q + (q - g) the product would stay exact and
+    // nothing would be rounded to 8 bits here (the fp32 conversion below would then round a second time).
+#pragma clang fp contract(off)
     const double c = 35184372088833.0;            // 2^45 + 1
     const double g0 = c * q0, g1 = c * q1;
     f32x2_t v;

@@ -205,3 +205,26 @@ def test_random_schedules(oracle, seed):
     x = wl.cast_io(wl.smooth_field(rng, B, H, W, D, 2.0) + 0.2 * rng.standard_normal((B, H, W, D)).astype(np.float32), dtype)
     sizes = rng.integers(1, 4, (B, H, W)) if seed % 3 == 0 else None
     run_case(oracle, x, dtype, passes, sizes=sizes, tag=f"fuzz{seed}")
+
+
+def test_pair_merge_near_a_rounding_tie(oracle):
+    """A three-token merge whose mean sits on a bf16 rounding boundary except for a term 2^-24 times smaller: the
+    intermediate token of the fused pair must be rounded from the exact fp64 mean, once (an fp32 stop on the way
+    would swallow the small term and resolve the tie the other way)."""
+    D = 64
+    rng = np.random.default_rng(12)
+    x = (0.05 * rng.standard_normal((1, 3, 2, D))).astype(np.float32)
+    sizes = np.ones((1, 3, 2), np.int64)
+    sizes[0, 1, :] = 2                                   # the destination row counts double: S = 4 per column
+    a, b = -0.197265625, -0.380859375                    # (a + 2 b) / 4 = -245.5 * 2^-10: a tie at bf16 resolution
+    for ch in range(32):
+        scale = 2.0 ** (ch % 7 - 3)
+        sign = -1.0 if ch & 8 else 1.0
+        nudge = (1.0 if ch & 16 else -1.0) * 2.0 ** -26   # pushes the mean off the tie, towards or away from "even"
+        x[0, 0, 0, ch], x[0, 1, 0, ch], x[0, 2, 0, ch] = sign * a * scale, sign * b * scale, nudge * scale
+        x[0, :, 1, ch] = 0.01 * scale                     # the neighbour the W pass merges it with: small, so one unit shows
+    x_io = wl.cast_io(x, "bf16")
+    np.testing.assert_array_equal(wl.widen(x_io, "bf16")[0, :, 0, :32], x[0, :, 0, :32])      # all chosen values are bf16 values
+    run_case(oracle, x_io, "bf16", [(H_AX, 2), (W_AX, 1)], sizes=sizes, tag="tie+tiny HW")
+    xt = np.ascontiguousarray(x_io.transpose(0, 2, 1, 3))
+    run_case(oracle, xt, "bf16", [(W_AX, 2), (H_AX, 1)], sizes=np.ascontiguousarray(sizes.transpose(0, 2, 1)), tag="tie+tiny WH")
