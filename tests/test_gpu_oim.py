@@ -225,6 +225,9 @@ def test_pair_merge_near_a_rounding_tie(oracle):
         x[0, :, 1, ch] = 0.01 * scale                     # the neighbour the W pass merges it with: small, so one unit shows
     x_io = wl.cast_io(x, "bf16")
     np.testing.assert_array_equal(wl.widen(x_io, "bf16")[0, :, 0, :32], x[0, :, 0, :32])      # all chosen values are bf16 values
+    run_case(oracle, x_io, "bf16", [(H_AX, 2)], sizes=sizes, tag="tie+tiny H (single halving pass)")
+    run_case(oracle, np.concatenate([x_io, x_io], axis=1), "bf16", [(H_AX, 2)], sizes=np.concatenate([sizes, sizes], axis=1),
+             tag="tie+tiny H (general pass: two of three sources)")
     run_case(oracle, x_io, "bf16", [(H_AX, 2), (W_AX, 1)], sizes=sizes, tag="tie+tiny HW")
     xt = np.ascontiguousarray(x_io.transpose(0, 2, 1, 3))
     run_case(oracle, xt, "bf16", [(W_AX, 2), (H_AX, 1)], sizes=np.ascontiguousarray(sizes.transpose(0, 2, 1)), tag="tie+tiny WH")

@@ -111,3 +111,21 @@ def test_wide_random_schedules(oracle, seed):
     x = wl.cast_io(wl.smooth_field(rng, B, H, W, D, 2.0) + 0.3 * rng.standard_normal((B, H, W, D)).astype(np.float32), dtype)
     sizes = rng.integers(1, 4, (B, H, W)) if seed % 3 == 0 else None
     run_wide(oracle, x, dtype, passes, radius, sizes=sizes, tag=f"fuzz{seed}")
+
+
+def test_wide_merge_near_a_rounding_tie(oracle):
+    """Means that sit on a bf16 rounding boundary except for a term 2^-24 times smaller, through the wide merge."""
+    D = 64
+    rng = np.random.default_rng(12)
+    x = (0.05 * rng.standard_normal((1, 3, 2, D))).astype(np.float32)
+    sizes = np.ones((1, 3, 2), np.int64)
+    sizes[0, 1, :] = 2
+    a, b = -0.197265625, -0.380859375                    # (a + 2 b) / 4 = -245.5 * 2^-10
+    for ch in range(32):
+        scale = 2.0 ** (ch % 7 - 3)
+        sign = -1.0 if ch & 8 else 1.0
+        nudge = (1.0 if ch & 16 else -1.0) * 2.0 ** -26
+        x[0, 0, 0, ch], x[0, 1, 0, ch], x[0, 2, 0, ch] = sign * a * scale, sign * b * scale, nudge * scale
+    x_io = wl.cast_io(x, "bf16")
+    run_wide(oracle, x_io, "bf16", [(H_AX, 2)], 0, sizes=sizes, tag="tie+tiny")
+    run_wide(oracle, np.ascontiguousarray(x_io.transpose(0, 2, 1, 3)), "bf16", [(W_AX, 2)], 2, sizes=np.ascontiguousarray(sizes.transpose(0, 2, 1)), tag="tie+tiny W")
