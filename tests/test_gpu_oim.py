@@ -231,3 +231,16 @@ def test_pair_merge_near_a_rounding_tie(oracle):
     run_case(oracle, x_io, "bf16", [(H_AX, 2), (W_AX, 1)], sizes=sizes, tag="tie+tiny HW")
     xt = np.ascontiguousarray(x_io.transpose(0, 2, 1, 3))
     run_case(oracle, xt, "bf16", [(W_AX, 2), (H_AX, 1)], sizes=np.ascontiguousarray(sizes.transpose(0, 2, 1)), tag="tie+tiny WH")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_large_sizes(oracle, dtype):
+    """Sizes far beyond anything a merge schedule produces (up to 10^6 per token; sums stay below 2^31): the fp64
+    weighted mean stays exact in its products and must still match bit for bit (bf16) / to 1e-5 (fp32)."""
+    rng = np.random.default_rng(21)
+    B, H, W, D = 2, 10, 12, 72
+    x = wl.cast_io(wl.smooth_field(rng, B, H, W, D, 2.0) + 0.1 * rng.standard_normal((B, H, W, D)).astype(np.float32), dtype)
+    sizes = rng.integers(1, 10 ** 6, (B, H, W))
+    run_case(oracle, x, dtype, [(W_AX, 6), (H_AX, 5)], sizes=sizes, tag="large sizes pair")
+    run_case(oracle, x, dtype, [(W_AX, 2), (H_AX, 2), (W_AX, 2)], sizes=sizes, tag="large sizes m=2")
+    run_case(oracle, x, dtype, [(H_AX, 5)], sizes=sizes, tag="large sizes single")
