@@ -455,7 +455,12 @@ oim_halve_pair(const T* __restrict__ x, const int32_t* __restrict__ sizes_in, Pa
     zero_tok(T0); zero_tok(T1); zero_tok(T2); zero_tok(T3);
     int s0 = 0, s1 = 0, s2 = 0, s3 = 0;
     unsigned took_a = 0, took_c = 0;                              // bit k: row k absorbed its a / its c
-#pragma unroll 1
+    // the four rows unrolled: the compiler renames T0..T3 instead of moving 10 registers per token and row
+    // (measured: 35.3 -> 34.2 us on 8 x 64 x 64 x 1280 bf16)
+#ifndef LUVC_OIM_UNROLL
+#define LUVC_OIM_UNROLL 4
+#endif
+#pragma unroll LUVC_OIM_UNROLL
     for (int k = 0; k < 4; ++k) {
         const int r = r0 + k;
         TokT Tn;
