@@ -225,3 +225,47 @@ def test_score_and_prune_random_shapes(oracle, seed):
         want = np.sort(np.argsort(-g[b], kind="stable")[:k])
         np.testing.assert_array_equal(pr["kept_idx"][b].cpu().numpy(), want)
         np.testing.assert_array_equal(to_host_f64(pr["x"][b]), to_host_f64(xd[b])[want])
+
+
+def test_calls_from_several_host_threads():
+    """Four host threads, each with a stream, workspace and outputs of its own, run score + prune side by side:
+    every result must equal, bit for bit, what one thread computes alone (the library keeps per-call counters in a
+    shared device array handed out in slots, and its error and timing state per thread)."""
+    import threading
+    rng = np.random.default_rng(99)
+    B, N, D, sigma, keep = 3, 1024, 160, 60, 100
+    xs = [to_dev(wl.cast_io(rng.standard_normal((B, N, D)).astype(np.float32), "bf16"), "bf16") for _ in range(4)]
+    want = []
+    for x in xs:
+        sc = lv.luvc_spu_score(x, sigma, True)
+        pr = lv.luvc_spu_prune(x, sc, keep)
+        torch.cuda.synchronize()
+        want.append((sc.clone(), pr["kept_idx"].clone(), pr["x"].clone()))
+    errors = []
+
+    def worker(k):
+        try:
+            torch.cuda.set_device(0)
+            st = torch.cuda.Stream()
+            ws = torch.empty(lv.luvc_spu_workspace_bytes(B, N, D, lv.LUVC_BF16, sigma), dtype=torch.uint8, device="cuda")
+            sc = torch.empty((B, N), dtype=torch.float32, device="cuda")
+            out = dict(kept_idx=torch.empty((B, keep), dtype=torch.int32, device="cuda"),
+                       x=torch.empty((B, keep, D), dtype=torch.bfloat16, device="cuda"))
+            for it in range(30):
+                sc.fill_(float("nan"))
+                st.wait_stream(torch.cuda.current_stream())
+                lv.luvc_spu_score(xs[k], sigma, True, workspace=ws, stream=st, out=sc)
+                lv.luvc_spu_prune(xs[k], sc, keep, stream=st, out=out)
+                st.synchronize()
+                if not (torch.equal(sc, want[k][0]) and torch.equal(out["kept_idx"], want[k][1]) and torch.equal(out["x"], want[k][2])):
+                    errors.append((k, it))
+                    return
+        except Exception as e:                    # surfaces in the main thread below
+            errors.append((k, repr(e)))
+
+    threads = [threading.Thread(target=worker, args=(k,)) for k in range(4)]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join()
+    assert not errors, errors
