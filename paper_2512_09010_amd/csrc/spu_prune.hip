@@ -183,7 +183,6 @@ spu_prune_fused(const unsigned char* __restrict__ x, const float* __restrict__ s
                 int64_t row_bytes_in, int64_t row_bytes_out, int32_t* __restrict__ kept_idx, unsigned char* __restrict__ x_out,
                 const int32_t* __restrict__ origin_in /* [B,N] or null: identity */, int32_t* __restrict__ origin_out /* [B,n_keep] or null */)
 {
-    __shared__ uint32_t keys[kFusedMaxN];
     __shared__ int32_t kept[kFusedMaxN];
     __shared__ int hist[4][256];                       // one histogram per digit pass: none has to be cleared in between
     __shared__ uint32_t wave_tot[4];
@@ -192,14 +191,14 @@ spu_prune_fused(const unsigned char* __restrict__ x, const float* __restrict__ s
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int g = blockIdx.x, G = gridDim.x, b = blockIdx.y;
     const float* s = scores + (int64_t)b * N;
-    for (int n = tid; n < N; n += kFusedThreads) keys[n] = score_key(s[n]);
-    hist[0][tid] = 0; hist[1][tid] = 0; hist[2][tid] = 0; hist[3][tid] = 0;
-    __syncthreads();
-    // thread tid owns the K consecutive tokens tid * K .. tid * K + K - 1
+    // thread tid owns the K consecutive tokens tid * K .. tid * K + K - 1 and reads them straight from memory
+    // (a wavefront covers 64 K consecutive scores; a few KB per sample, served by the caches)
     const int K = (N + kFusedThreads - 1) / kFusedThreads, n0 = tid * K;
     uint32_t key[kFusedKeys];
 #pragma unroll
-    for (int i = 0; i < kFusedKeys; ++i) key[i] = (i < K && n0 + i < N) ? keys[n0 + i] : 0u;
+    for (int i = 0; i < kFusedKeys; ++i) key[i] = (i < K && n0 + i < N) ? score_key(s[n0 + i]) : 0u;
+    hist[0][tid] = 0; hist[1][tid] = 0; hist[2][tid] = 0; hist[3][tid] = 0;
+    __syncthreads();
 
     uint32_t prefix = 0, mask = 0;
     int remaining = n_keep;                            // still to pick among keys matching the prefix
