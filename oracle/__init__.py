@@ -4,8 +4,14 @@ TEST INFRASTRUCTURE ONLY: imported by ``tests/``, by ``__graft_entry__.smoke``
 and by the ``cpu_baseline`` leg of ``bench.py``.  The product package never
 imports this module and this module never imports the product package.
 
-The functions below only marshal numpy arrays into ``luvc_oracle.c``; every
-step of the method lives in the C file.
+Most functions below only marshal numpy arrays into ``luvc_oracle.c``, where the
+arithmetic of the method lives (similarity, matching, merge, transform, mask,
+energy, selection).  Three small pieces of the later rows are written here in
+python instead, each a few lines of integer bookkeeping around those C routines:
+``cascade_keeps`` (keep counts of an SPU cascade), ``spu_stage`` (one cascade
+stage = the C score and prune routines plus the composition of origins) and
+``plan_anyres`` (the aspect-ratio schedule).  They are pinned like the rest
+(``tests/test_oracle_spu.py``, ``tests/test_oracle_oim.py``).
 """
 from __future__ import annotations
 

@@ -5,7 +5,7 @@ import torch
 
 from paper_2512_09010_amd import binding as lv
 from paper_2512_09010_amd import workloads as wl
-from gpu_util import OIM_MARGIN, RTOL, assert_close, round_mode, to_dev, to_host_f64
+from gpu_util import OIM_MARGIN, RTOL, assert_close, oim_reference, round_mode, to_dev, to_host_f64
 
 pytestmark = pytest.mark.gpu
 W_AX, H_AX = 1, 0
@@ -13,24 +13,21 @@ W_AX, H_AX = 1, 0
 
 def run_case(oracle, x_io, dtype, passes, sizes=None, tag=""):
     print(f"[oim] {tag} shape={x_io.shape} dtype={dtype} passes={passes}", flush=True)
-    ref = oracle.oim_merge(wl.widen(x_io, dtype), passes, sizes=sizes, round_mode=round_mode(oracle, dtype))
     s_dev = None if sizes is None else torch.from_numpy(np.ascontiguousarray(sizes, dtype=np.int32)).cuda()
     out = lv.luvc_oim_merge(to_dev(x_io, dtype), passes, sizes=s_dev)
     torch.cuda.synchronize()
+    # the oracle; where one of its decisions is closer than fp64 can resolve, the alternative the GPU took is
+    # accepted there if it is within OIM_MARGIN of the best one (gpu_util.oim_reference)
+    ref = oim_reference(oracle, wl.widen(x_io, dtype), passes, out["merged_map"].cpu().numpy(), dtype, sizes=sizes)
     assert out["x"].shape == ref["x"].shape
-    # a gap of exactly 0 is an exact tie, decided by the lower-position rule on both sides; only a
-    # tiny non-zero gap leaves the decision to rounding
-    if ref["margin"] > OIM_MARGIN or ref["margin"] == 0.0:
-        np.testing.assert_array_equal(out["sizes"].cpu().numpy().astype(np.int64), ref["sizes"])
-        np.testing.assert_array_equal(out["merged_map"].cpu().numpy(), ref["merged_map"])
-        np.testing.assert_array_equal(out["kept_map"].cpu().numpy(), ref["kept_map"])
-        got = to_host_f64(out["x"])
-        assert_close(got, ref["x"], RTOL[dtype], f"{tag} features")
-        if dtype == "bf16":
-            # the merge is evaluated in fp64 and rounded once, so bf16 outputs agree to the bit
-            np.testing.assert_array_equal(got, ref["x"])
-    else:
-        pytest.skip(f"decision margin {ref['margin']:.3e} below {OIM_MARGIN}: maps not unique")
+    np.testing.assert_array_equal(out["sizes"].cpu().numpy().astype(np.int64), ref["sizes"])
+    np.testing.assert_array_equal(out["merged_map"].cpu().numpy(), ref["merged_map"])
+    np.testing.assert_array_equal(out["kept_map"].cpu().numpy(), ref["kept_map"])
+    got = to_host_f64(out["x"])
+    assert_close(got, ref["x"], RTOL[dtype], f"{tag} features")
+    if dtype == "bf16":
+        # the merge is evaluated in fp64 and rounded once, so bf16 outputs agree to the bit
+        np.testing.assert_array_equal(got, ref["x"])
     return out, ref
 
 
@@ -244,3 +241,25 @@ def test_large_sizes(oracle, dtype):
     run_case(oracle, x, dtype, [(W_AX, 6), (H_AX, 5)], sizes=sizes, tag="large sizes pair")
     run_case(oracle, x, dtype, [(W_AX, 2), (H_AX, 2), (W_AX, 2)], sizes=sizes, tag="large sizes m=2")
     run_case(oracle, x, dtype, [(H_AX, 5)], sizes=sizes, tag="large sizes single")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_decisions_closer_than_the_arithmetic_resolves(oracle, dtype):
+    """Destinations that are scaled copies of each other: a source between them sees two cosines that are equal in exact
+    arithmetic and differ, if at all, in the last bit of an fp64 evaluation.  The oracle's margin is then tiny without
+    being zero, the GPU's operation order may resolve such a decision the other way, and the comparison has to accept
+    that alternative (and nothing else)."""
+    rng = np.random.default_rng(31)
+    B, H, W, D = 2, 8, 10, 64
+    x = rng.standard_normal((B, H, W, D)).astype(np.float32)
+    x = (x.view(np.uint32) & np.uint32(0xFFF00000)).view(np.float32).copy()   # 4 significant bits: times 15 is still a bf16 value
+    x[:, :, 3] = 3 * x[:, :, 1]                                              # destination 3 of every row is a multiple of destination 1
+    x[:, :, 7] = 3 * x[:, :, 5]
+    x[:, 5] = 5 * x[:, 3]                                                    # and row 5 a multiple of row 3
+    x_io = wl.cast_io(x, dtype)
+    np.testing.assert_array_equal(wl.widen(x_io, dtype), x)
+    margins = []
+    for passes in ([(W_AX, 5)], [(W_AX, 5), (H_AX, 4)], [(H_AX, 4), (W_AX, 5)], [(W_AX, 2), (H_AX, 2)], [(H_AX, 3)]):
+        run_case(oracle, x_io, dtype, passes, tag="scaled copies")
+        margins.append(oracle.oim_merge(wl.widen(x_io, dtype), passes, round_mode=round_mode(oracle, dtype))["margin"])
+    assert min(margins) <= OIM_MARGIN                                       # the case does visit the situation it is written for

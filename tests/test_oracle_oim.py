@@ -268,6 +268,112 @@ def test_rounding_between_passes(oracle):
     np.testing.assert_array_equal(r["x"].ravel(), wl.widen(wl.cast_io(vals.astype(np.float32), "bf16"), "bf16"))
 
 
+def exact_round(v: float, sig_bits: int, min_exp: int = -126) -> float:
+    """Nearest value with `sig_bits` significant bits (ties to the even significand), gradual underflow below
+    2^min_exp - in exact rational arithmetic.  bfloat16: 8 bits, fp32: 24 bits, both with min_exp = -126."""
+    from fractions import Fraction
+    if v == 0.0:
+        return v
+    a = abs(Fraction(v))                                          # a double converts exactly
+    e = a.numerator.bit_length() - a.denominator.bit_length()
+    if Fraction(2) ** e > a:
+        e -= 1                                                    # 2^e <= a < 2^(e+1)
+    quantum = Fraction(2) ** (max(e, min_exp) - (sig_bits - 1))
+    n, rem = divmod(a, quantum)
+    n = int(n)
+    if rem * 2 > quantum or (rem * 2 == quantum and n % 2 == 1):
+        n += 1
+    r = float(n * quantum)                                        # at most 24 bits: exact
+    return -r if v < 0 else r
+
+
+@pytest.mark.parametrize("mode,bits", [("ROUND_BF16", 8), ("ROUND_F32", 24)])
+def test_output_rounding_next_to_ties_against_exact_arithmetic(oracle, mode, bits):
+    # The merge of a pass is rounded ONCE from fp64 to the storage type.  The mistake to catch is a rounding in two
+    # steps (fp64 -> fp32 -> bf16): it only shows on fp64 values that sit next to a rounding boundary of the storage
+    # type without being fp32 values themselves, so the cases are built there: boundary +- a relative 2^-20 ... 2^-50,
+    # both signs, normal binades from 2^-126 up to 2^100 and the subnormal range of the storage types.
+    vals = []
+    for e in (-140, -133, -130, -127, -126, -100, -20, -1, 0, 1, 7, 60, 100):
+        for n in (2 ** (bits - 1), 2 ** (bits - 1) + 1, 2 ** (bits - 1) + 2, 3 * 2 ** (bits - 2) + 1, 2 ** bits - 2, 2 ** bits - 1):
+            quantum = 2.0 ** (max(e, -126) - (bits - 1))
+            if e < -126:
+                n = n >> (-126 - e)                               # subnormal: fewer significant bits, same quantum
+            tie = (n + 0.5) * quantum                             # exact in fp64: at most 25 significant bits
+            for k in (20, 24, 25, 30, 40, 50):
+                for sgn in (1.0, -1.0):
+                    vals += [sgn * tie, sgn * tie * (1.0 + 2.0 ** -k), sgn * tie * (1.0 - 2.0 ** -k),
+                             sgn * np.nextafter(tie, np.inf), sgn * np.nextafter(tie, 0.0)]
+    vals = np.array(vals)
+    assert (np.abs(vals).astype(np.float32).astype(np.float64) != np.abs(vals)).sum() > vals.size // 2   # mostly not fp32 values
+    got = oracle.oim_merge(vals.reshape(1, 1, 1, -1), [(W_AX, 0)], round_mode=getattr(oracle, mode))["x"].ravel()
+    want = np.array([exact_round(float(v), bits) for v in vals])
+    np.testing.assert_array_equal(got, want)
+    # and through the merge itself: a mean (a + b) / 2 that lands next to a boundary.  b = 2 v - a with a on the
+    # storage grid; whenever that difference is exact in fp64 the oracle forms exactly v again and must round it as above
+    a = np.array([exact_round(float(v), bits) for v in vals])
+    b = 2.0 * vals - a
+    ok = np.isfinite(b) & ((a + b) / 2.0 == vals)
+    assert ok.sum() > vals.size // 2
+    line = np.stack([a[ok], b[ok]], 0).reshape(1, 1, 2, -1)
+    got = oracle.oim_merge(line, [(W_AX, 1)], round_mode=getattr(oracle, mode))["x"].ravel()
+    np.testing.assert_array_equal(got, want[ok])
+
+
+# ---------------------------------------------------------------- the reported decision margin
+
+def test_margin_hand_cases(oracle):
+    inf = float("inf")
+    e1, e2 = [1.0, 0.0], [0.0, 1.0]
+    # line of five: sources 0, 2, 4, destinations 1, 3.  Source 2 = (3, 4) sees cos 3/5 with e1 and 4/5 with e2: the only
+    # choice between two candidates on the line (the sources at the ends have one neighbour each)
+    line = np.array([e1, e1, [3.0, 4.0], e2, e2]).reshape(1, 1, 5, 2)
+    r = oracle.oim_merge(line, [(W_AX, 3)])
+    assert r["margin"] == 4.0 / 5.0 - 3.0 / 5.0
+    np.testing.assert_array_equal(r["merged_map"][0], [0, 0, 1, 1, 1])
+    # 0 < m < number of sources adds the gap between the last merged and the best unmerged source:
+    # scores are 1 (source 0), 4/5 (source 2), 1 (source 4) -> m = 2 merges 0 and 4, gap 1 - 4/5; m = 1: exact tie
+    r = oracle.oim_merge(line, [(W_AX, 2)])
+    assert r["margin"] == min(4.0 / 5.0 - 3.0 / 5.0, 1.0 - 4.0 / 5.0)
+    np.testing.assert_array_equal(r["merged_map"][0], [0, 0, 1, 2, 2])
+    assert oracle.oim_merge(line, [(W_AX, 1)])["margin"] == 0.0
+    # the selection gap alone: scores 1, 24/25, 7/25 with every candidate gap wider than the selection gap
+    line = np.array([e1, e1, [24.0, 7.0], e2, [1.0, 1.0]]).reshape(1, 1, 5, 2)
+    s2, s4 = 24.0 / 25.0, 1.0 / np.sqrt(2.0)
+    cand2 = 24.0 / 25.0 - 7.0 / 25.0
+    assert oracle.oim_merge(line, [(W_AX, 1)])["margin"] == pytest.approx(min(cand2, 1.0 - s2), abs=1e-15)
+    assert oracle.oim_merge(line, [(W_AX, 2)])["margin"] == pytest.approx(min(cand2, s2 - s4), abs=1e-15)
+    assert oracle.oim_merge(line, [(W_AX, 3)])["margin"] == pytest.approx(cand2, abs=1e-15)
+    # no decision at all: a line of three with every source merged, or nothing merged on a line of two
+    three = np.array([e1, [1.0, 1.0], e2]).reshape(1, 1, 3, 2)
+    assert oracle.oim_merge(three, [(W_AX, 2)])["margin"] == inf
+    assert oracle.oim_merge(three[:, :, :2], [(W_AX, 0)])["margin"] == inf
+    # exact ties report a gap of zero (the lower position wins them)
+    u = np.array([1.0, 2.0, -1.0])
+    assert oracle.oim_merge(np.array([u, u, u, u]).reshape(1, 1, 4, 3), [(W_AX, 2)])["margin"] == 0.0
+    # a column pass sees the same gaps as the row pass on the transposed grid
+    assert oracle.oim_merge(line.transpose(0, 2, 1, 3).copy(), [(H_AX, 2)])["margin"] == oracle.oim_merge(line, [(W_AX, 2)])["margin"]
+
+
+def test_margin_is_the_minimum_over_lines_images_and_passes(oracle):
+    rng = np.random.default_rng(40)
+    x = rng.standard_normal((3, 6, 8, 5))
+    per_image = [oracle.oim_merge(x[b:b + 1], [(W_AX, 3)])["margin"] for b in range(3)]
+    per_line = [oracle.oim_merge(x[1:2, h:h + 1], [(W_AX, 3)])["margin"] for h in range(6)]
+    assert oracle.oim_merge(x, [(W_AX, 3)])["margin"] == min(per_image)
+    assert per_image[1] == min(per_line)
+    one = oracle.oim_merge(x, [(W_AX, 3)])
+    second = oracle.oim_merge(one["x"], [(H_AX, 2)], sizes=one["sizes"])
+    both = oracle.oim_merge(x, [(W_AX, 3), (H_AX, 2)])
+    assert both["margin"] == min(one["margin"], second["margin"])
+    # independent value: smallest gap between the best and the second-best cosine of a source (radius 1, every source
+    # merged, so no selection gap), from unit vectors
+    y = rng.standard_normal((1, 1, 9, 4))
+    unit = y[0, 0] / np.linalg.norm(y[0, 0], axis=-1, keepdims=True)
+    gaps = [abs(float(unit[a] @ unit[a - 1]) - float(unit[a] @ unit[a + 1])) for a in range(2, 8, 2)]
+    assert oracle.oim_merge(y, [(W_AX, 5)])["margin"] == pytest.approx(min(gaps), abs=1e-14)
+
+
 def test_invalid_schedules(oracle):
     x = rnd((1, 4, 4, 2))
     with pytest.raises(ValueError):
