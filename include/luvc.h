@@ -176,9 +176,9 @@ size_t luvc_spu_workspace_bytes(int B, int N, int D, luvc_dtype dtype, int sigma
  *   scores      device [B,N] fp32
  * Arithmetic is fp32 (bf16 is a storage type only).  The sum over channels is taken in a fixed order:
  * the same input gives the same bits on every call.
- * Concurrency: calls may overlap on different streams as long as each has its own workspace and at most
- * 64 of them are in flight on one GPU (the single-launch kernels keep per-sample completion counters in
- * a static device array that is handed out in 64 slots).
+ * Concurrency: calls may overlap on different streams, or with replays of a captured graph, as long as each call
+ * in flight has its own workspace.  The workspace may hold anything when the call starts (the completion counters
+ * the single-launch kernels keep in it recognise stale contents), and nothing in it is needed afterwards.
  */
 luvc_status luvc_spu_score(const void* x, int B, int N, int D, int64_t row_stride, luvc_dtype dtype,
                            int sigma, int use_hamming, float* scores,

@@ -197,7 +197,7 @@ template <typename T, int Q, bool POW2, bool ALIGNED>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((Q == 9 || (Q == 15 && sizeof(T) == 2)) ? 3 : LUVC_FFT_WAVES)))
 spu_fft16q(const T* __restrict__ x, int N, int D, int64_t row_stride, int sigma, int use_hamming,
            float* __restrict__ partial /* [B, n_tiles, N] */, float* __restrict__ gpartial /* [B, n_groups, N] */,
-           unsigned int* __restrict__ done /* [B][1 + n_groups], zero between calls */, float* __restrict__ scores /* [B, N] */)
+           const TileSync sy, float* __restrict__ scores /* [B, N] */)
 {
     using pio = pair_io<T>;
     constexpr int N1 = 16 * Q;
@@ -349,6 +349,7 @@ spu_fft16q(const T* __restrict__ x, int N, int D, int64_t row_stride, int sigma,
     };
     forward(0, std::true_type{});
     for (int n2 = 1; n2 < N2; ++n2) forward(n2, std::false_type{});
+    const tile_tag_t seen = tiles_look<4>(sy, b, tile, n_tiles);     // no loads follow: nothing waits behind this one
     // ------------------------------------------------------------------ mask (Eq. 5-6) with the 1/N of Eq. 7
 #pragma unroll
     for (int kb = 0; kb < Q; ++kb) {
@@ -397,6 +398,7 @@ spu_fft16q(const T* __restrict__ x, int N, int D, int64_t row_stride, int sigma,
         __syncthreads();
     };
     inverse(0, std::true_type{});
+    tiles_claim<4>(sy, b, tile, n_tiles, seen);
     for (int n2 = 1; n2 < N2; ++n2) inverse(n2, std::false_type{});
     float* pout = partial + ((int64_t)b * n_tiles + tile) * N;
     for (int n = tid; n < N; n += 256) {         // n = N2 (Q j + t') + n2
@@ -406,7 +408,7 @@ spu_fft16q(const T* __restrict__ x, int N, int D, int64_t row_stride, int sigma,
         tile_store(pout + n, eperm[(n2 * Q + tq) * 16 + j]);
     }
     // ------------------------------------------------------------------ Eq. 8 across the channel tiles
-    tiles_to_scores<256, 4>(partial, gpartial, done, scores, b, tile, n_tiles, N, &is_last);
+    tiles_to_scores<256, 4>(partial, gpartial, sy, scores, b, tile, n_tiles, N, &is_last);
 }
 
 static size_t fft_lds_bytes(int N, int Q, int sigma)
@@ -428,7 +430,7 @@ static int fft_pick_q(int N, int sigma)
 bool spu_fft_supported(int N, int sigma) { return fft_pick_q(N, sigma) != 0; }
 
 luvc_status spu_score_fft(const void* x, int B, int N, int D, int64_t row_stride, luvc_dtype dt, int sigma, int use_hamming,
-                          float* partial, float* gpartial, int n_tiles, float* scores, hipStream_t st)
+                          float* partial, float* gpartial, const TileSync& sy, int n_tiles, float* scores, hipStream_t st)
 {
     const int Q = fft_pick_q(N, sigma);
     const size_t lds = fft_lds_bytes(N, Q, sigma);
@@ -436,24 +438,13 @@ luvc_status spu_score_fft(const void* x, int B, int N, int D, int64_t row_stride
     // channel pairs are fetched with one access when every pair is naturally aligned
     const size_t es = dt == LUVC_F32 ? 4 : 2;
     const bool aligned = (row_stride % 2 == 0) && ((uintptr_t)x % (2 * es) == 0) && (D % 2 == 0);
-    const int n_groups = spu_tile_groups(n_tiles);
-    if (n_groups + 1 > kSlotCounters) { set_error("D=%d exceeds the supported width of the fft path", D); return LUVC_ERR_UNSUPPORTED; }
-    const int per_launch = kSlotCounters / (n_groups + 1);       // samples whose counters fit one slot
-#define LUVC_FFT(TT, QQ, P2, AL) LUVC_LAUNCH("spu_fft16q", (spu_fft16q<TT, QQ, P2, AL>), grid, dim3(256), lds, st, (const TT*)xs, N, D, row_stride, sigma, use_hamming, ps, gs, done, ss)
+    if (n_tiles > 65535) { set_error("D=%d exceeds the supported width of the fft path", D); return LUVC_ERR_UNSUPPORTED; }
+    const dim3 grid((unsigned)n_tiles, (unsigned)B);
+#define LUVC_FFT(TT, QQ, P2, AL) LUVC_LAUNCH("spu_fft16q", (spu_fft16q<TT, QQ, P2, AL>), grid, dim3(256), lds, st, (const TT*)x, N, D, row_stride, sigma, use_hamming, partial, gpartial, sy, scores)
 #define LUVC_FFT_A(TT, QQ, P2) do { if (aligned) LUVC_FFT(TT, QQ, P2, true); else LUVC_FFT(TT, QQ, P2, false); } while (0)
 #define LUVC_FFT_T(TT) do { if (Q == 16) { if (pow2) LUVC_FFT_A(TT, 16, true); else LUVC_FFT_A(TT, 16, false); } \
                             else if (Q == 15) LUVC_FFT_A(TT, 15, false); else LUVC_FFT_A(TT, 9, false); } while (0)
-    for (int b0 = 0; b0 < B; b0 += per_launch) {
-        const int nb = B - b0 < per_launch ? B - b0 : per_launch;
-        const dim3 grid((unsigned)n_tiles, (unsigned)nb);
-        const char* xs = (const char*)x + (size_t)b0 * N * row_stride * es;
-        float* ps = partial + (size_t)b0 * n_tiles * N;
-        float* gs = gpartial + (size_t)b0 * n_groups * N;
-        float* ss = scores + (size_t)b0 * N;
-        unsigned int* done = spu_take_counters();
-        if (!done) return LUVC_ERR_HIP;
-        if (dt == LUVC_F32) LUVC_FFT_T(float); else LUVC_FFT_T(bf16_t);
-    }
+    if (dt == LUVC_F32) LUVC_FFT_T(float); else LUVC_FFT_T(bf16_t);
 #undef LUVC_FFT_T
 #undef LUVC_FFT_A
 #undef LUVC_FFT

@@ -15,8 +15,9 @@
 //   spu_dense_fused all of the above in one launch, for samples whose tables and pass-band spectrum of a
 //                   64-channel tile fit in LDS (small N and sigma, where the launches themselves dominate)
 #include <atomic>
-
+#include <chrono>
 #include <cstdlib>
+#include <random>
 #include <type_traits>
 
 #include "common.hpp"
@@ -188,7 +189,7 @@ static size_t dense_fused_cap()
 template <typename T>
 __global__ void __launch_bounds__(64 * kDfWaves)
 spu_dense_fused(const T* __restrict__ x, int N, int D, int64_t row_stride, int sigma, int use_hamming,
-                float* __restrict__ partial, float* __restrict__ gpartial, unsigned int* __restrict__ done,
+                float* __restrict__ partial, float* __restrict__ gpartial, const TileSync sy,
                 float* __restrict__ scores)
 {
     using tr = io_traits<T>;
@@ -324,6 +325,7 @@ spu_dense_fused(const T* __restrict__ x, int N, int D, int64_t row_stride, int s
 
     // ---- inverse (Eq. 7, +k and -k paired) and energy over the tile's channels (Eq. 8)
     float* pout = partial + ((int64_t)b * n_tiles + tile) * N;
+    const tile_tag_t seen = tiles_look<1>(sy, b, tile, n_tiles);      // no loads follow: nothing waits behind this one
     for (int pb = wave; pb < P; pb += kDfWaves * kDfTok) {
         float accA[kDfTok], accB[kDfTok];
 #pragma unroll
@@ -356,32 +358,24 @@ spu_dense_fused(const T* __restrict__ x, int N, int D, int64_t row_stride, int s
                 if (p > 0 && 2 * p != N) tile_store(pout + (N - p), eq);
             }
         }
+        if (pb == wave) tiles_claim<1>(sy, b, tile, n_tiles, seen);    // by the end of the loop the swap has long been served
     }
-    tiles_to_scores<64 * kDfWaves, 1>(partial, gpartial, done, scores, b, tile, n_tiles, N, &flag);
+    tiles_to_scores<64 * kDfWaves, 1>(partial, gpartial, sy, scores, b, tile, n_tiles, N, &flag);
 }
 
-// Completion counters of the samples in flight (one per sample and one per tile group of a sample), one
-// set per call slot.  They are zero whenever no call that uses the slot is running (see spu_tiles.hpp).
-constexpr int kSlots = 64;
-__device__ unsigned int g_spu_done[kSlots * kSlotCounters];
-static std::atomic<unsigned> g_spu_slot{0};
-
-unsigned int* spu_take_counters()
+// Tags of the arrival words (spu_tiles.hpp): one per launch, from a process-wide sequence that starts at a random
+// 48-bit value, so that whatever a workspace held before cannot pass for a word of this launch.  Never zero.
+tile_tag_t spu_next_tag()
 {
-    // every GPU holds its own copy of the array at its own address: looked up once per device, with that device current
-    constexpr int kMaxDev = 64;
-    static std::atomic<unsigned int*> base_of[kMaxDev];
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDev) { set_error("spu score: no current device"); return nullptr; }
-    unsigned int* base = base_of[dev].load(std::memory_order_acquire);
-    if (!base) {
-        if (hipGetSymbolAddress((void**)&base, HIP_SYMBOL(g_spu_done)) != hipSuccess || !base) {
-            check_launch("spu score (counters)");
-            return nullptr;
-        }
-        base_of[dev].store(base, std::memory_order_release);
+    static std::atomic<unsigned long long> next{[] {
+        std::random_device rd;
+        const unsigned long long t = (unsigned long long)std::chrono::steady_clock::now().time_since_epoch().count();
+        return (((unsigned long long)rd() << 32) ^ (unsigned long long)rd() ^ (t * 0x9E3779B97F4A7C15ull));
+    }()};
+    for (;;) {
+        const tile_tag_t tag = next.fetch_add(1, std::memory_order_relaxed) & 0xffffffffffffull;
+        if (tag) return tag;
     }
-    return base + (size_t)(g_spu_slot.fetch_add(1) % kSlots) * kSlotCounters;
 }
 
 // ------------------------------------------------------------------ host side
@@ -400,6 +394,7 @@ SpuLayout spu_layout(int B, int N, int D, int sigma)
     L.Fs = off;      off += align_up(sizeof(float) * spec);
     L.partial = off; off += align_up(sizeof(float) * (size_t)B * L.n_tiles * N);
     L.gpartial = off; off += align_up(sizeof(float) * (size_t)B * spu_tile_groups(L.n_tiles) * N);
+    L.arrive = off;  off += align_up(sizeof(tile_tag_t) * (size_t)B * (spu_tile_groups(L.n_tiles) + 1));
     L.bytes = off;
     return L;
 }
@@ -415,25 +410,20 @@ luvc_status spu_score_dense(const void* x, int B, int N, int D, int64_t row_stri
     float* Fc = (float*)(ws + L.Fc);
     float* Fs = (float*)(ws + L.Fs);
     float* partial = (float*)(ws + L.partial);
-    if (L.fast) return spu_score_fft(x, B, N, D, row_stride, dt, sigma, use_hamming, partial, (float*)(ws + L.gpartial), L.n_tiles, scores, st);
-    if (dense_fused_lds(N, sigma) <= dense_fused_cap() && spu_tile_groups(L.n_tiles) + 1 <= kSlotCounters) {
-        const int per_launch = kSlotCounters / (spu_tile_groups(L.n_tiles) + 1);
-        const size_t es = dt == LUVC_F32 ? 4 : 2;
-        for (int b0 = 0; b0 < B; b0 += per_launch) {
-            const int nb = B - b0 < per_launch ? B - b0 : per_launch;
-            const dim3 grid((unsigned)L.n_tiles, (unsigned)nb);
-            const char* xs = (const char*)x + (size_t)b0 * N * row_stride * es;
-            float* ps = partial + (size_t)b0 * L.n_tiles * N;
-            float* gs = (float*)(ws + L.gpartial) + (size_t)b0 * spu_tile_groups(L.n_tiles) * N;
-            unsigned int* done = spu_take_counters();
-            if (!done) return LUVC_ERR_HIP;
-            if (dt == LUVC_F32)
-                LUVC_LAUNCH("spu_dense_fused", (spu_dense_fused<float>), grid, dim3(64 * kDfWaves), dense_fused_lds(N, sigma), st,
-                            (const float*)xs, N, D, row_stride, sigma, use_hamming, ps, gs, done, scores + (size_t)b0 * N);
-            else
-                LUVC_LAUNCH("spu_dense_fused", (spu_dense_fused<bf16_t>), grid, dim3(64 * kDfWaves), dense_fused_lds(N, sigma), st,
-                            (const bf16_t*)xs, N, D, row_stride, sigma, use_hamming, ps, gs, done, scores + (size_t)b0 * N);
-        }
+    float* gpartial = (float*)(ws + L.gpartial);
+    if (L.n_tiles > 65535) { set_error("D=%d exceeds the supported width", D); return LUVC_ERR_UNSUPPORTED; }
+    TileSync sy;
+    sy.arrive = (tile_tag_t*)(ws + L.arrive);
+    sy.tag = spu_next_tag();
+    if (L.fast) return spu_score_fft(x, B, N, D, row_stride, dt, sigma, use_hamming, partial, gpartial, sy, L.n_tiles, scores, st);
+    if (dense_fused_lds(N, sigma) <= dense_fused_cap()) {
+        const dim3 grid((unsigned)L.n_tiles, (unsigned)B);
+        if (dt == LUVC_F32)
+            LUVC_LAUNCH("spu_dense_fused", (spu_dense_fused<float>), grid, dim3(64 * kDfWaves), dense_fused_lds(N, sigma), st,
+                        (const float*)x, N, D, row_stride, sigma, use_hamming, partial, gpartial, sy, scores);
+        else
+            LUVC_LAUNCH("spu_dense_fused", (spu_dense_fused<bf16_t>), grid, dim3(64 * kDfWaves), dense_fused_lds(N, sigma), st,
+                        (const bf16_t*)x, N, D, row_stride, sigma, use_hamming, partial, gpartial, sy, scores);
         return check_launch("spu score (dense, one launch)");
     }
     LUVC_LAUNCH("spu_tables", spu_tables, dim3((unsigned)((N + 255) / 256)), dim3(256), 0, st, N, sigma, use_hamming, tw, gk, gm);

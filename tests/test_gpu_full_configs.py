@@ -130,3 +130,41 @@ def test_step_replayed_from_a_hip_graph():
         assert torch.equal(out["merged_map"], eager_o["merged_map"]) and torch.equal(out["kept_map"], eager_o["kept_map"]), rep
         assert torch.equal(scores.view(torch.int32), eager_s.view(torch.int32)), rep
         assert torch.equal(pr["kept_idx"], eager_p["kept_idx"]) and torch.equal(pr["x"].view(torch.int16), eager_p["x"].view(torch.int16)), rep
+
+
+@pytest.mark.parametrize("B,N,D,sigma", [(2, 1024, 544, 102), (2, 196, 320, 4)])      # fft path (two tile groups), one-launch direct path
+def test_graph_replays_beside_eager_score_calls(B, N, D, sigma):
+    """A captured score launch replayed on one stream while more than 64 eager score calls run on another: every call
+    owns its workspace (completion counters included), so nothing is shared between calls in flight and every result
+    must carry the bits of a call that ran alone.  The workspaces start out holding different garbage."""
+    rng = np.random.default_rng(N + D)
+    xs = to_dev(wl.cast_io(rng.standard_normal((B, N, D)).astype(np.float32), "bf16"), "bf16")
+    xs2 = to_dev(wl.cast_io(rng.standard_normal((B, N, D)).astype(np.float32), "bf16"), "bf16")
+    alone = lv.luvc_spu_score(xs, sigma, True)
+    alone2 = lv.luvc_spu_score(xs2, sigma, True)
+    torch.cuda.synchronize()
+    need = max(256, lv.luvc_spu_workspace_bytes(B, N, D, lv.LUVC_BF16, sigma))
+    ws_g = torch.empty(need, dtype=torch.uint8, device="cuda"); ws_g.fill_(0x01)
+    ws_e = torch.empty(need, dtype=torch.uint8, device="cuda"); ws_e.fill_(0xA5)
+    sc_g = torch.empty_like(alone)
+    side, other = torch.cuda.Stream(), torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            lv.luvc_spu_score(xs, sigma, True, workspace=ws_g, stream=torch.cuda.current_stream(), out=sc_g)
+    torch.cuda.synchronize()
+    outs = [torch.empty_like(alone2) for _ in range(72)]
+    for rep in range(3):
+        print(f"[graph+eager] N={N} round {rep}", flush=True)
+        sc_g.zero_()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(side):
+            for _ in range(24):
+                g.replay()
+        with torch.cuda.stream(other):
+            for o in outs[rep * 24:(rep + 1) * 24]:
+                lv.luvc_spu_score(xs2, sigma, True, workspace=ws_e, stream=other, out=o)
+        torch.cuda.synchronize()
+        assert torch.equal(sc_g.view(torch.int32), alone.view(torch.int32)), rep
+        for k, o in enumerate(outs[rep * 24:(rep + 1) * 24]):
+            assert torch.equal(o.view(torch.int32), alone2.view(torch.int32)), (rep, k)
