@@ -184,6 +184,23 @@ luvc_status luvc_spu_score(const void* x, int B, int N, int D, int64_t row_strid
                            int sigma, int use_hamming, float* scores,
                            void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/*
+ * luvc_spu_score for callers that cannot allocate device memory and so have no workspace to pass: code that runs
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernels, same arithmetic and
+ * the same bits in `scores` as luvc_spu_score; the scratch lives in a static device array of
+ * LUVC_SPU_STATIC_SCRATCH_BYTES inside the library (one copy per GPU, held until the process ends).  The call
+ * allocates and frees no device memory and calls no library routine that does.
+ *   x, B, N, D, row_stride, dtype, sigma, use_hamming, scores, hip_stream   as for luvc_spu_score
+ * Returns LUVC_ERR_WORKSPACE (nothing enqueued) when luvc_spu_workspace_bytes(B, N, D, dtype, sigma) exceeds
+ * LUVC_SPU_STATIC_SCRATCH_BYTES; the message carries both figures.
+ * Every call on a GPU uses that GPU's one array: two calls that overlap in time on one GPU (different streams, or a
+ * captured graph replayed while another call runs) race on it and give wrong scores.  Calls on one stream, one
+ * after the other, are fine, whatever their sizes.
+ */
+#define LUVC_SPU_STATIC_SCRATCH_BYTES (8u << 20)
+luvc_status luvc_spu_score_static(const void* x, int B, int N, int D, int64_t row_stride, luvc_dtype dtype,
+                                  int sigma, int use_hamming, float* scores, void* hip_stream);
+
 /* Number of tokens to keep for a keep ratio: floor(ratio*N + 0.5) clamped to [1, N]. */
 int luvc_keep_count(int N, double keep_ratio);
 

@@ -18,7 +18,7 @@ LUVC_F32, LUVC_BF16 = 0, 1
 
 EXPORTS = ("luvc_version", "luvc_last_error", "luvc_oim_plan", "luvc_oim_workspace_bytes", "luvc_oim_merge",
            "luvc_oim_wide_workspace_bytes", "luvc_oim_merge_wide",
-           "luvc_oim_keyed_workspace_bytes", "luvc_oim_merge_keyed", "luvc_value_enhance", "luvc_spu_workspace_bytes", "luvc_spu_score", "luvc_keep_count", "luvc_spu_prune",
+           "luvc_oim_keyed_workspace_bytes", "luvc_oim_merge_keyed", "luvc_value_enhance", "luvc_spu_workspace_bytes", "luvc_spu_score", "luvc_spu_score_static", "luvc_keep_count", "luvc_spu_prune",
            "luvc_spu_cascade_keeps", "luvc_spu_stage",
            "luvc_oim_plan_anyres", "luvc_oim_ragged_workspace_bytes", "luvc_oim_merge_ragged",
            "luvc_spu_ragged_workspace_bytes", "luvc_spu_stage_ragged",
@@ -71,6 +71,8 @@ def lib() -> ctypes.CDLL:
     L.luvc_spu_workspace_bytes.restype = sz
     L.luvc_spu_score.argtypes = [vp, i, i, i, i64, i, i, i, vp, vp, sz, vp]
     L.luvc_spu_score.restype = i
+    L.luvc_spu_score_static.argtypes = [vp, i, i, i, i64, i, i, i, vp, vp]
+    L.luvc_spu_score_static.restype = i
     L.luvc_keep_count.argtypes = [i, ctypes.c_double]
     L.luvc_keep_count.restype = i
     L.luvc_spu_prune.argtypes = [vp, vp, i, i, i, i64, i, i, vp, vp, vp, sz, vp]
@@ -286,6 +288,21 @@ def luvc_spu_score(x, sigma: int, use_hamming: bool = True, workspace=None, stre
         out = torch.empty((B, N), dtype=torch.float32, device=x.device)
     _check(lib().luvc_spu_score(_ptr(x), B, N, D, x.stride(1), code, int(sigma), int(bool(use_hamming)), _ptr(out),
                                 _ptr(workspace), workspace.numel(), _stream(stream)))
+    return out
+
+
+SPU_STATIC_SCRATCH_BYTES = 8 << 20
+
+
+def luvc_spu_score_static(x, sigma: int, use_hamming: bool = True, stream=None, out=None):
+    """luvc_spu_score on the library's static scratch (no workspace; pass `out` to keep the call free of allocations)."""
+    import torch
+    assert x.is_cuda and x.dim() == 3 and x.stride(2) == 1 and x.stride(0) == x.shape[1] * x.stride(1)
+    B, N, D = x.shape
+    if out is None:
+        out = torch.empty((B, N), dtype=torch.float32, device=x.device)
+    _check(lib().luvc_spu_score_static(_ptr(x), B, N, D, x.stride(1), _dtype_code(x), int(sigma), int(bool(use_hamming)),
+                                       _ptr(out), _stream(stream)))
     return out
 
 
