@@ -3,9 +3,10 @@
 
 A step = luvc_oim_merge (every call of the workload's schedule) + luvc_spu_score + luvc_spu_prune
 over one batch of seeded synthetic input that is already resident in HBM.  Prints ONE JSON line:
-tokens/s (visual tokens entering OIM per second), the HBM roofline of the dominant kernel measured
-with HIP events on the launch stream, and the CPU oracle timed on a bounded sample of the same
-workload on this host's cores.
+tokens/s (visual tokens entering OIM per second) of the four target workloads (`configs`, headline =
+the largest), the roofline of the headline's dominant kernel measured with HIP events on the launch
+stream, and the CPU oracle timed on the same chain on this host's cores (all cores and one thread),
+which also checks the GPU's chained OIM -> projection -> SPU run.
 """
 from __future__ import annotations
 
@@ -27,8 +28,9 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", type=int, default=1, help="workload 0..4 of BASELINE.json (default 1: the metric's config)")
-    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
+    ap.add_argument("--config", type=int, default=None,
+                    help="time one workload 0..4 of BASELINE.json only (default: 1..4, headline on the largest, cfg2)")
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle leg (timing and the check of the chained run)")
     ap.add_argument("--no-pipelined", dest="pipelined", action="store_false", help="skip the two-stream leg")
     ap.add_argument("--oim-wide", action="store_true",
                     help="also time luvc_oim_merge_wide on the workload's grid in the paper's setting (whole-line matching, merge number 2, three operations)")
@@ -38,41 +40,33 @@ def parse():
     return ap.parse_args()
 
 
-def main():
-    args = parse()
-    if args.gpus != 1:
-        print("bench.py: this build is single-GPU by design (the path shards over the batch with no exchange); "
-              "run with --gpus 1", file=sys.stderr)
-        sys.exit(2)
-    import numpy as np
-    import torch
-    from paper_2512_09010_amd import binding as lv
-    from paper_2512_09010_amd import workloads as wl
+HEADLINE = 2            # the largest of the four target workloads (46 080 tokens per step)
+TRAFFIC_FILE = os.path.join("profiles", "hbm_traffic.json")
 
-    lv.lib()                                       # fail loudly if the HIP library is not built
-    torch.cuda.set_device(0)
+
+def run_config(cfg, args, lv, wl, torch, np):
+    """Times the step of one workload.  Returns (json-ready result, context for the optional legs)."""
     dev = torch.device("cuda:0")
-    w = wl.workload(args.config)
+    w = wl.workload(cfg)
     tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
     es = 2 if w.dtype == "bf16" else 4
+    code = lv.LUVC_BF16 if w.dtype == "bf16" else lv.LUVC_F32
 
     def upload(a):
         if w.dtype == "bf16":
             return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).view(torch.bfloat16).to(dev)
         return torch.from_numpy(a).to(dev)
 
+    def download(t):
+        if t.dtype == torch.bfloat16:
+            return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+        return t.cpu().numpy()
+
     t0 = time.time()
     x_oim_host = wl.oim_input(w)
-    x_spu_host = wl.spu_input(w)
-    x_oim0, x_spu0 = upload(x_oim_host), upload(x_spu_host)
-    set_bytes = x_oim0.numel() * es + x_spu0.numel() * es
-    n_rot = max(2, int(np.ceil(args.rotate_mb * 1e6 / set_bytes)))
-    xs_oim = [x_oim0] + [x_oim0.clone() for _ in range(n_rot - 1)]
-    xs_spu = [x_spu0] + [x_spu0.clone() for _ in range(n_rot - 1)]
-    gen_s = time.time() - t0
+    x_oim0 = upload(x_oim_host)
 
     # ---- preallocate every output and workspace: nothing is allocated inside the timed region
-    code = lv.LUVC_BF16 if w.dtype == "bf16" else lv.LUVC_F32
     calls = []
     H, W = w.H, w.W
     ws_bytes = 256
@@ -93,12 +87,36 @@ def main():
                   x=torch.empty((w.spu_B, w.n_keep, w.spu_D), dtype=tdt, device=dev))
     stream = torch.cuda.current_stream()
 
-    def step(i, ev=None):
-        x, sizes = xs_oim[i % n_rot], None
-        if ev: ev[0].record(stream)
+    def oim(x, st):
+        sizes = None
         for passes, out in calls:
-            lv.luvc_oim_merge(x, passes, sizes=sizes, workspace=workspace, stream=stream, out=out)
+            lv.luvc_oim_merge(x, passes, sizes=sizes, workspace=workspace, stream=st, out=out)
             x, sizes = out["x"], out["sizes"]
+
+    # ---- the chain the configurations describe, once, untimed: OIM on the GPU, the merged tokens projected to the LLM
+    # width on the host (input generation, workloads.spu_input_from_merged), SPU on the result.  The SPU calls of the
+    # timed steps read this tensor.
+    oim(x_oim0, stream)
+    torch.cuda.synchronize()
+    oim_out_host = [{k: download(v) for k, v in out.items()} for _, out in calls]
+    merged_vals = wl.bf16_bits_to_f32(oim_out_host[-1]["x"]) if w.dtype == "bf16" else oim_out_host[-1]["x"]
+    x_spu_host = wl.spu_input_from_merged(w, merged_vals)
+    x_spu0 = upload(x_spu_host)
+    lv.luvc_spu_score(x_spu0, w.sigma, True, workspace=workspace_spu, stream=stream, out=scores)
+    lv.luvc_spu_prune(x_spu0, scores, w.n_keep, stream=stream, out=pr_out)
+    torch.cuda.synchronize()
+    chain_gpu = dict(oim=oim_out_host, scores=scores.cpu().numpy().copy(), kept_idx=pr_out["kept_idx"].cpu().numpy().copy(),
+                     x_keep=download(pr_out["x"]).copy())
+
+    set_bytes = x_oim0.numel() * es + x_spu0.numel() * es
+    n_rot = max(2, int(np.ceil(args.rotate_mb * 1e6 / set_bytes)))
+    xs_oim = [x_oim0] + [x_oim0.clone() for _ in range(n_rot - 1)]
+    xs_spu = [x_spu0] + [x_spu0.clone() for _ in range(n_rot - 1)]
+    gen_s = time.time() - t0
+
+    def step(i, ev=None):
+        if ev: ev[0].record(stream)
+        oim(xs_oim[i % n_rot], stream)
         if ev: ev[1].record(stream)
         xs = xs_spu[i % n_rot]
         lv.luvc_spu_score(xs, w.sigma, True, workspace=workspace_spu, stream=stream, out=scores)
@@ -138,10 +156,7 @@ def main():
         s_oim, s_spu = torch.cuda.Stream(), torch.cuda.Stream()
 
         def step2(i):
-            x, sizes = xs_oim[i % n_rot], None
-            for passes, out in calls:
-                lv.luvc_oim_merge(x, passes, sizes=sizes, workspace=workspace, stream=s_oim, out=out)
-                x, sizes = out["x"], out["sizes"]
+            oim(xs_oim[i % n_rot], s_oim)
             xs = xs_spu[i % n_rot]
             lv.luvc_spu_score(xs, w.sigma, True, workspace=workspace_spu, stream=s_spu, out=scores)
             lv.luvc_spu_prune(xs, scores, w.n_keep, stream=s_spu, out=pr_out)
@@ -189,7 +204,9 @@ def main():
     if n1 and w.spu_N <= 4096:
         n2 = w.spu_N // n1
         # per packed channel pair: N2 forward + N2 inverse N1-point transforms (5 P log2 P each), the
-        # pass-band accumulation and expansion (8 flops per bin and subsequence, both ways), the energy
+        # pass-band accumulation and expansion (8 flops per bin and subsequence, both ways), the energy.
+        # This is the work of Eq. 4-8 as the transform decomposition states it; a kernel that reaches the same
+        # scores with fewer operations is credited with these, not with its own count.
         fft_flops = w.spu_B * (w.spu_D / 2) * (2 * n2 * 5 * n1 * np.log2(n1) + 2 * 8 * n2 * L + 4 * w.spu_N)
     work = {
         "oim_halve_pair": (oim_bytes, None, "hbm"), "oim_halve": (oim_bytes, None, "hbm"),
@@ -198,7 +215,7 @@ def main():
         "spu_gather": (prune_bytes, None, "hbm"), "spu_prune_fused": (prune_bytes, None, "hbm"),
     }
     try:
-        with open(os.path.join(ROOT, "profiles", "hbm_traffic.json")) as f:
+        with open(os.path.join(ROOT, TRAFFIC_FILE)) as f:
             measured_traffic = json.load(f).get(w.name, {})
     except (OSError, ValueError):
         measured_traffic = {}
@@ -234,6 +251,9 @@ def main():
         roofline = {"bound": "hbm", "kernel": dom["kernel"], "achieved": dom.get("hbm_GBps"), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": dom.get("hbm_frac"), "traffic": dom.get("traffic_bytes_per_launch"), "avg_us": dom["avg_us"],
                     "algorithmic_bytes": dom.get("algorithmic_bytes_per_launch")}
+    # the traffic figures are NOT measured by this run: hardware counters need a profiler run of their own
+    roofline["traffic_source"] = (f"{TRAFFIC_FILE} (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of an earlier run of this script, "
+                                  "calibrated on copy kernels; see the summaries beside it)") if roofline.get("traffic") else None
     roofline["timing"] = f"start/stop HIP events attached by the library to every dispatch on the launch stream, {n_prof} steps after the timed region"
     roofline["kernels"] = kernels
     roofline["whole_step"] = {"algorithmic_bytes": sum(alg.values()),
@@ -242,25 +262,70 @@ def main():
     roofline["calls_ms"] = {n: round(float(v), 5) for n, v in zip(["oim", "spu_score", "spu_prune"], seg_mean)}
 
     result = {
-        "metric": "visual tokens compressed/sec (OIM+SPU) on 1 MI355X; % of peak HBM GB/s", "value": round(tokens_per_s, 1), "unit": "tokens/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "value": round(tokens_per_s, 1), "ms_per_step": round(ms_per_step, 5), "dtype": w.dtype,
         "config": {"workload": w.name, "tokens_per_step": w.tokens_in, "oim": f"{w.grids}x{w.H}x{w.W}x{w.D}",
                    "spu": f"{w.spu_B}x{w.spu_N}x{w.spu_D}", "n_keep": w.n_keep, "sigma": w.sigma,
+                   "spu_input": "the GPU's own OIM output, projected on the host to the SPU width",
                    "rotating_input_sets": n_rot, "input_gen_s": round(gen_s, 1)},
         "roofline": roofline,
         "pct_of_peak_hbm": round(100.0 * roofline["whole_step"]["frac"], 2),      # algorithmic bytes of the whole step / step time / 8 TB/s
     }
     if pipelined:
         result["pipelined"] = pipelined
+    ctx = dict(w=w, xs_oim=xs_oim, xs_spu=xs_spu, n_rot=n_rot, tdt=tdt, code=code, es=es, stream=stream,
+               x_oim_host=x_oim_host, x_spu_host=x_spu_host, chain_gpu=chain_gpu)
+    return result, ctx
+
+
+def brief(r):
+    """One workload's line of the `configs` table."""
+    ro = r["roofline"]
+    return {"workload": r["config"]["workload"], "tokens_per_step": r["config"]["tokens_per_step"], "ms_per_step": r["ms_per_step"],
+            "value": r["value"], "unit": "tokens/s", "pct_of_peak_hbm": r["pct_of_peak_hbm"],
+            "pipelined_ms_per_step": r.get("pipelined", {}).get("ms_per_step"),
+            "roofline": {k: ro.get(k) for k in ("bound", "kernel", "achieved", "peak", "unit", "frac", "avg_us", "traffic", "traffic_source")},
+            "kernels_us_per_step": {k["kernel"]: k["us_per_step"] for k in ro["kernels"]}}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU by design (the path shards over the batch with no exchange); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    from paper_2512_09010_amd import binding as lv
+    from paper_2512_09010_amd import workloads as wl
+
+    lv.lib()                                       # fail loudly if the HIP library is not built
+    torch.cuda.set_device(0)
+    cfgs = [args.config] if args.config is not None else [1, 2, 3, 4]
+    head = args.config if args.config is not None else HEADLINE
+    table, head_result, ctx = [], None, None
+    for c in cfgs:
+        r, cx = run_config(c, args, lv, wl, torch, np)
+        table.append(brief(r))
+        if c == head:
+            head_result, ctx = r, cx
+        else:
+            del cx
+            torch.cuda.empty_cache()
+    w = ctx["w"]
+    result = {"metric": "visual tokens compressed/sec (OIM+SPU) on 1 MI355X; % of peak HBM GB/s", "value": head_result["value"],
+              "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": head_result["ms_per_step"],
+              "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": head_result["dtype"], "data": "synthetic",
+              "config": head_result["config"], "roofline": head_result["roofline"], "pct_of_peak_hbm": head_result["pct_of_peak_hbm"],
+              "configs": table}
+    if "pipelined" in head_result:
+        result["pipelined"] = head_result["pipelined"]
     if args.oim_wide:
-        result["oim_wide"] = oim_wide_leg(lv, torch, w, xs_oim, n_rot, tdt, code, es, stream, args.steps)
-
+        result["oim_wide"] = oim_wide_leg(lv, torch, w, ctx["xs_oim"], ctx["n_rot"], ctx["tdt"], ctx["code"], ctx["es"], ctx["stream"], args.steps)
     if args.next_rows:
-        result["next_rows"] = next_rows_leg(lv, torch, w, xs_oim, xs_spu, n_rot, tdt, code, es, stream, min(args.steps, 50))
-
+        result["next_rows"] = next_rows_leg(lv, torch, w, ctx["xs_oim"], ctx["xs_spu"], ctx["n_rot"], ctx["tdt"], ctx["code"], ctx["es"],
+                                            ctx["stream"], min(args.steps, 50))
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(w, x_oim_host, x_spu_host)
+        result["cpu_baseline"], result["chained"] = cpu_baseline(w, ctx["x_oim_host"], ctx["chain_gpu"])
     print(json.dumps(result))
 
 
@@ -407,35 +472,93 @@ def next_rows_leg(lv, torch, w, xs_oim, xs_spu, n_rot, tdt, code, es, stream, st
     return res
 
 
-def cpu_baseline(w, x_oim_host, x_spu_host):
-    """The oracle as it stands, on a bounded sample of the same inputs, on this host's cores."""
+def _omp_threads(n):
+    """Sets the thread count of the OpenMP runtime the oracle is linked against; returns the count now in force."""
+    import ctypes
+    try:
+        g = ctypes.CDLL("libgomp.so.1")
+        if n:
+            g.omp_set_num_threads(int(n))
+        return int(g.omp_get_max_threads())
+    except OSError:
+        return None
+
+
+def cpu_baseline(w, x_oim_host, chain_gpu):
+    """The oracle as it stands on the same chain the GPU ran once before the timed steps (OIM, the merged tokens
+    projected to the SPU width, SPU score, keep): timed on all of this host's cores over the whole batch and on one
+    thread over one SPU sample's share of it, and compared with what the GPU produced.  Returns (cpu_baseline, chained)."""
     import numpy as np
     import oracle
     from paper_2512_09010_amd import workloads as wl
 
-    n_s = min(w.spu_B, 16)                                  # SPU samples (each an independent OpenMP job)
-    frac = n_s / w.spu_B
-    n_g = max(1, int(round(w.grids * frac)))
+    OIM_MARGIN, SPU_MARGIN = 1e-10, 2e-6          # as in tests/gpu_util.py
     rm = oracle.ROUND_BF16 if w.dtype == "bf16" else oracle.ROUND_F32
-    xo = wl.widen(x_oim_host[:n_g], w.dtype)
-    xs = wl.widen(x_spu_host[:n_s], w.dtype)
     oracle.lib()
-    t0 = time.perf_counter()
-    cur, sizes = xo, None
-    for passes in w.oim_calls:
-        r = oracle.oim_merge(cur, passes, sizes=sizes, round_mode=rm)
-        cur, sizes = r["x"], r["sizes"]
-    t1 = time.perf_counter()
-    sc = oracle.spu_score(xs, w.sigma, True)
-    oracle.spu_prune(sc, w.n_keep, xs)
-    t2 = time.perf_counter()
-    tokens = n_g * w.H * w.W
-    ncpu = os.cpu_count() or 1
-    omp = int(os.environ.get("OMP_NUM_THREADS", ncpu))
-    return {"value": round(tokens / (t2 - t0), 1), "unit": "tokens/s", "cores": omp, "kind": "oracle",
-            "threads_used": {"oim": omp, "spu": int(min(omp, n_s))},
-            "sample": f"{n_g} of {w.grids} OIM grids + {n_s} of {w.spu_B} SPU samples of {w.name}",
-            "seconds": {"oim": round(t1 - t0, 3), "spu": round(t2 - t1, 3)}}
+    omp = _omp_threads(0) or int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+
+    def chain(x_io, n_samples):
+        """oracle OIM calls -> projection -> oracle score + keep on the first n_samples samples' share of the batch."""
+        g = n_samples * (w.grids // w.spu_B)
+        t0 = time.perf_counter()
+        cur, sizes, outs = wl.widen(x_io[:g], w.dtype), None, []
+        for passes in w.oim_calls:
+            r = oracle.oim_merge(cur, passes, sizes=sizes, round_mode=rm)
+            outs.append(r)
+            cur, sizes = r["x"], r["sizes"]
+        t1 = time.perf_counter()
+        sub = wl.Workload(**{**w.__dict__, "grids": g, "spu_B": n_samples})
+        xs = wl.spu_input_from_merged(sub, cur)            # input generation, not timed
+        xs64 = wl.widen(xs, w.dtype)
+        t2 = time.perf_counter()
+        sc = oracle.spu_score(xs64, w.sigma, True)
+        pr = oracle.spu_prune(sc, w.n_keep, xs64)
+        t3 = time.perf_counter()
+        return dict(oim=outs, xs=xs, scores=sc, prune=pr, t_oim=t1 - t0, t_spu=t3 - t2, tokens=g * w.H * w.W)
+
+    full = chain(x_oim_host, w.spu_B)
+    _omp_threads(1)
+    one = chain(x_oim_host, 1)
+    _omp_threads(omp)
+    base = {"value": round(full["tokens"] / (full["t_oim"] + full["t_spu"]), 1), "unit": "tokens/s", "cores": omp, "kind": "oracle",
+            "threads_used": {"oim": int(min(omp, w.grids)), "spu": int(min(omp, w.spu_B))},
+            "sample": f"all {w.grids} OIM grids + all {w.spu_B} SPU samples of {w.name} (the chained run)",
+            "seconds": {"oim": round(full["t_oim"], 3), "spu": round(full["t_spu"], 3)},
+            "one_thread": {"value": round(one["tokens"] / (one["t_oim"] + one["t_spu"]), 1), "unit": "tokens/s", "cores": 1,
+                           "sample": f"{w.grids // w.spu_B} OIM grid(s) + 1 SPU sample of {w.name}",
+                           "seconds": {"oim": round(one["t_oim"], 3), "spu": round(one["t_spu"], 3)}}}
+
+    # ---- the GPU's chained run against the oracle's
+    maps_equal, bits_equal, margin = True, True, float("inf")
+    for ref, got in zip(full["oim"], chain_gpu["oim"]):
+        margin = min(margin, float(ref["margin"]))
+        maps_equal &= bool(np.array_equal(got["merged_map"], ref["merged_map"]) and np.array_equal(got["kept_map"], ref["kept_map"])
+                           and np.array_equal(got["sizes"].astype(np.int64), ref["sizes"]))
+        gx = wl.widen(got["x"], w.dtype)
+        bits_equal &= bool(np.array_equal(gx, ref["x"])) if w.dtype == "bf16" else bool(np.allclose(gx, ref["x"], rtol=1e-5, atol=0))
+    gpu_xs = wl.spu_input_from_merged(w, wl.bf16_bits_to_f32(chain_gpu["oim"][-1]["x"]) if w.dtype == "bf16" else chain_gpu["oim"][-1]["x"])
+    same_input = bool(np.array_equal(gpu_xs, full["xs"]))
+    ref_sc, ref_pr = full["scores"], full["prune"]
+    if not same_input:                              # the oracle then judges the SPU calls on the tensor the GPU read
+        xs64 = wl.widen(gpu_xs, w.dtype)
+        ref_sc = oracle.spu_score(xs64, w.sigma, True)
+        ref_pr = oracle.spu_prune(ref_sc, w.n_keep, xs64)
+    got_sc = chain_gpu["scores"].astype(np.float64)
+    rel = float(np.max(np.abs(got_sc - ref_sc) / np.maximum(np.abs(ref_sc), 1e-300)))
+    own = oracle.spu_prune(got_sc, w.n_keep)["kept_idx"]
+    chained = {"what": "luvc_oim_merge -> host projection -> luvc_spu_score -> luvc_spu_prune on the GPU's own bits, once, untimed, "
+                       "against the oracle run on the same chain",
+               "oim_maps_and_sizes_equal": maps_equal, "oim_features_equal": bits_equal, "oim_decision_margin": margin,
+               "oim_margin_threshold": OIM_MARGIN, "spu_input_equal": same_input, "score_max_rel_err": rel, "score_tolerance": 1e-5,
+               "kept_idx_equal_to_selection_on_own_scores": bool(np.array_equal(chain_gpu["kept_idx"], own)),
+               "kept_idx_equal_to_oracle": bool(np.array_equal(chain_gpu["kept_idx"], ref_pr["kept_idx"])),
+               "keep_boundary_margin": float(ref_pr["margin"]), "keep_margin_threshold": SPU_MARGIN,
+               "kept_rows_equal": bool(np.array_equal(wl.widen(chain_gpu["x_keep"], w.dtype), ref_pr["x"]))
+               if np.array_equal(chain_gpu["kept_idx"], ref_pr["kept_idx"]) else None}
+    chained["ok"] = bool((maps_equal and bits_equal or margin <= OIM_MARGIN) and rel <= 1e-5
+                         and chained["kept_idx_equal_to_selection_on_own_scores"]
+                         and (chained["kept_idx_equal_to_oracle"] or ref_pr["margin"] <= SPU_MARGIN))
+    return base, chained
 
 
 if __name__ == "__main__":

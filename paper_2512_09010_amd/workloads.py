@@ -242,3 +242,18 @@ def spu_input(w: Workload, reseed: int = 0) -> np.ndarray:
     a = a.reshape(w.spu_B, w.group * Ho * Wo, w.D)
     assert a.shape[1] == w.spu_N, (a.shape, w.spu_N)
     return cast_io(project(rng, a, w.spu_D), w.dtype)
+
+
+def spu_input_from_merged(w: Workload, merged: np.ndarray, reseed: int = 0) -> np.ndarray:
+    """SPU input of a workload made from a merged grid: [grids,Ho,Wo,D] values (any float type) ->
+    [spu_B, spu_N, spu_D] in the I/O dtype, by the seeded Gaussian projection to the LLM width.
+
+    This is the hand-over the configurations describe (OIM output, projected, then SPU); whoever calls it
+    supplies the merged tokens - the HIP path its own, the oracle its own.  Sequence order: tile-major /
+    frame-major, then raster.
+    """
+    rng = np.random.default_rng(w.seed + 700 + 1000 * reseed)
+    Ho, Wo = w.out_grid()
+    a = np.asarray(merged, dtype=np.float32).reshape(w.spu_B, w.group * Ho * Wo, w.D)
+    assert a.shape[1] == w.spu_N, (a.shape, w.spu_N)
+    return cast_io(project(rng, a, w.spu_D), w.dtype)

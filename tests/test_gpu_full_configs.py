@@ -168,3 +168,58 @@ def test_graph_replays_beside_eager_score_calls(B, N, D, sigma):
         assert torch.equal(sc_g.view(torch.int32), alone.view(torch.int32)), rep
         for k, o in enumerate(outs[rep * 24:(rep + 1) * 24]):
             assert torch.equal(o.view(torch.int32), alone2.view(torch.int32)), (rep, k)
+
+
+@pytest.mark.parametrize("i", [0, 1, 2, 3, 4])
+def test_chained_step_on_the_gpus_own_bits(oracle, i):
+    """The chain the configurations describe, end to end on one set of bits: every OIM call reads the previous call's
+    GPU output, the merged tokens are projected on the host to the SPU width (input generation), and the score and the
+    keep run on that tensor.  The oracle runs the same chain from the same input on its own."""
+    w = wl.workload(i)
+    code = lv.LUVC_BF16 if w.dtype == "bf16" else lv.LUVC_F32
+    for reseed in range(4):
+        x = wl.oim_input(w, reseed)
+        print(f"[chain] {w.name} reseed={reseed}", flush=True)
+        cur_ref, sizes_ref, margin = wl.widen(x, w.dtype), None, np.inf
+        for passes in w.oim_calls:
+            ref = oracle.oim_merge(cur_ref, passes, sizes=sizes_ref, round_mode=round_mode(oracle, w.dtype))
+            margin = min(margin, ref["margin"])
+            cur_ref, sizes_ref = ref["x"], ref["sizes"]
+        xs_ref = wl.spu_input_from_merged(w, cur_ref, reseed)
+        xs64 = wl.widen(xs_ref, w.dtype)
+        sc_ref = oracle.spu_score(xs64, w.sigma, True)
+        pr_ref = oracle.spu_prune(sc_ref, w.n_keep, xs64)
+        if margin > OIM_MARGIN and pr_ref["margin"] > SPU_MARGIN:
+            break
+        print(f"  decision gap {margin:.3e}, keep-boundary gap {pr_ref['margin']:.3e}: reseeding", flush=True)
+    else:
+        pytest.fail("no seed with unique decisions found")
+    cur, sizes = to_dev(x, w.dtype), None
+    for passes in w.oim_calls:
+        out = lv.luvc_oim_merge(cur, passes, sizes=sizes)
+        cur, sizes = out["x"], out["sizes"]
+    torch.cuda.synchronize()
+    merged = to_host_f64(cur)
+    np.testing.assert_array_equal(sizes.cpu().numpy().astype(np.int64), sizes_ref)
+    if w.dtype == "bf16":
+        np.testing.assert_array_equal(merged, cur_ref)                          # so both sides project the same tokens
+    else:
+        np.testing.assert_allclose(merged, cur_ref, rtol=1e-5, atol=0)
+    xs = wl.spu_input_from_merged(w, merged, reseed)                            # the GPU's own bits, projected
+    xd = to_dev(xs, w.dtype)
+    scores = lv.luvc_spu_score(xd, w.sigma, True)
+    pr = lv.luvc_spu_prune(xd, scores, w.n_keep)
+    torch.cuda.synchronize()
+    if w.dtype == "f32" and not np.array_equal(xs, xs_ref):                     # fp32 merges may differ in the last place: judge the SPU calls on what they read
+        xs64 = wl.widen(xs, w.dtype)
+        sc_ref = oracle.spu_score(xs64, w.sigma, True)
+        pr_ref = oracle.spu_prune(sc_ref, w.n_keep, xs64)
+        assert pr_ref["margin"] > SPU_MARGIN
+    else:
+        np.testing.assert_array_equal(xs, xs_ref)
+    got = scores.cpu().numpy().astype(np.float64)
+    rel = np.abs(got - sc_ref) / np.abs(sc_ref)
+    print(f"  worst relative score error {rel.max():.3e}", flush=True)
+    assert rel.max() <= 1e-5
+    np.testing.assert_array_equal(pr["kept_idx"].cpu().numpy(), pr_ref["kept_idx"])
+    np.testing.assert_array_equal(to_host_f64(pr["x"]), pr_ref["x"])
