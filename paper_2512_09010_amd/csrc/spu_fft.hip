@@ -18,6 +18,17 @@
 // threads hold 16 points each for the radix-16 side, all 16 hold Q points each for the other side.
 // The pass-band accumulators F stay in registers across the N2 subsequences, so x is read exactly
 // once and nothing but N floats per tile is written.
+//
+// Thinned inverse.  The energy of a token over the channels of a tile, e[n] = sum_d x'[n,d]^2, is a trigonometric
+// polynomial of degree <= 2 sigma in n, so its values at the tokens n = dec * m (dec divides N2, N / dec >
+// 4 sigma) fix all N of them.  The inverse therefore runs on every dec-th subsequence first; the workgroup fills
+// in the tokens between with a Kaiser-windowed sinc (fp64 taps and sums; cut-off half the coarse rate, stop band
+// 140 dB down: design error 1e-7 of the energies around the token) and checks, token by token, that the value it
+// got is not small against the absolute sum  a[n] = sum |tap| e[m]  it came from: e^[n] >= a[n] / 32.  Rounding
+// errors of the e[m] (relative 2e-7 at most) reach e^[n] multiplied by at most a[n] / e^[n], so a tile that
+// passes hands over energies that are within 1e-5 of what the full inverse gives, and the sum over tiles
+// inherits the bound.  A tile with a token that fails (a token whose filtered channels all but vanish where its
+// neighbours' do not) runs the remaining subsequences and hands over what Eq. 7-8 say, as if dec were 1.
 #include <type_traits>
 
 #include "common.hpp"
@@ -188,26 +199,84 @@ __device__ __forceinline__ float row16_sum(float v)
     return v;
 }
 
+// ---- interpolation kernel of the thinned inverse
+// Kaiser window: I0 by its power series in z = x^2 / 4 (all terms positive; 40 terms cover x <= 16 to fp64 accuracy)
+constexpr int kI0Terms = 40;
+struct I0Coef {
+    double c[kI0Terms];
+    constexpr I0Coef() : c()
+    {
+        double f = 1.0;
+        for (int k = 0; k < kI0Terms; ++k) {
+            if (k) f /= (double)k * (double)k;
+            c[k] = f;                            // 1 / (k!)^2
+        }
+    }
+};
+__device__ __forceinline__ double bessel_i0(double x)
+{
+    constexpr I0Coef K{};
+    const double z = 0.25 * x * x;
+    double s = K.c[kI0Terms - 1];
+#pragma unroll
+    for (int k = kI0Terms - 2; k >= 0; --k) s = fma(s, z, K.c[k]);
+    return s;
+}
+constexpr double kKaiserAtten = 140.0;                           // dB
+constexpr double kKaiserBeta = 0.1102 * (kKaiserAtten - 8.7);    // 14.5
+constexpr double kPi = 3.14159265358979323846;
+constexpr double kCondition = 1.0 / 32.0;                        // a tile is interpolated only if e^[n] >= kCondition * a[n] for all n
+constexpr int kMaxTaps = 256;                                    // (dec - 1) * 2 H, doubles in LDS
+
+// Half-width (in coarse samples) of the kernel for Ns samples of a polynomial of degree <= 2 sigma: the transition
+// band runs from 2 sigma / Ns to 1 - 2 sigma / Ns cycles per coarse sample.  <= 0: Ns is too small.
+double interp_half_width(int Ns, int sigma)
+{
+    const double df = 1.0 - 4.0 * (double)sigma / (double)Ns;
+    if (df <= 0.0) return -1.0;
+    return 0.5 * ((kKaiserAtten - 8.0) / (2.285 * 2.0 * kPi * df) + 1.0);
+}
+// taps on each side of a token: ceil(hw), rounded up to a multiple of 4
+int interp_taps_half(double hw) { const int h = (int)hw + ((double)(int)hw < hw ? 1 : 0); return (h + 3) / 4 * 4; }
+
+// taps[(s - 1) * 2 H + i] = h(s / dec - (i - H + 1)), s = 1 .. dec - 1, i < 2 H;  h(u) = sinc(u) kaiser(u / hw)
+__device__ __forceinline__ void interp_build_taps(double* taps, int dec, int H, double hw)
+{
+    const int e = threadIdx.x;
+    if (e >= (dec - 1) * 2 * H) return;
+    const int s = e / (2 * H) + 1, i = e - (s - 1) * 2 * H, m = i - H + 1;
+    const double frac = (double)s / (double)dec, u = frac - (double)m, q = u / hw;
+    double h = 0.0;
+    if (q > -1.0 && q < 1.0) {
+        const double sn = (m & 1) ? -sinpi(frac) : sinpi(frac);        // sin(pi u)
+        h = sn / (kPi * u) * bessel_i0(kKaiserBeta * sqrt(1.0 - q * q)) / bessel_i0(kKaiserBeta);
+    }
+    taps[e] = h;
+}
+
 }  // namespace
 
 #ifndef LUVC_FFT_WAVES
 #define LUVC_FFT_WAVES 2
 #endif
-template <typename T, int Q, bool POW2, bool ALIGNED>
+template <typename T, int Q, bool POW2, bool ALIGNED, bool THIN>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((Q == 9 || (Q == 15 && sizeof(T) == 2)) ? 3 : LUVC_FFT_WAVES)))
 spu_fft16q(const T* __restrict__ x, int N, int D, int64_t row_stride, int sigma, int use_hamming,
+           int dec_arg /* THIN: the inverse starts with the subsequences n2 = 0, dec, 2 dec, ... */, int taps_h, double taps_hw,
            float* __restrict__ partial /* [B, n_tiles, N] */, float* __restrict__ gpartial /* [B, n_groups, N] */,
            const TileSync sy, float* __restrict__ scores /* [B, N] */)
 {
     using pio = pair_io<T>;
     constexpr int N1 = 16 * Q;
+    const int dec = THIN ? dec_arg : 1;
     extern __shared__ float2 smem[];
     float2* xbuf = smem;                         // [16][kRowPad]  exchange between the two passes
     float2* tw = smem + 16 * kRowPad;            // [N]    (cos, sin)(2 pi i / N)
     float2* tw1 = tw + N;                        // [N1]   (cos, sin)(2 pi i / N1)
     float* eperm = reinterpret_cast<float*>(tw1 + N1);      // [N2][Q t][16 j] energies of this tile
     float* gm = eperm + N;                       // [sigma + 1]  M[f] / N  (Eq. 5 with the 1/N of Eq. 7)
-    __shared__ int is_last;
+    double* taps = reinterpret_cast<double*>(smem + 16 * kRowPad + N + N1) + (N + sigma + 1 + 1) / 2;    // [(dec - 1) 2 H]
+    __shared__ int is_last, ill;                 // ill: some token of the tile cannot be interpolated
     const int tid = threadIdx.x, c = tid & 15, t = tid >> 4;
     // neighbouring channel tiles share 128-byte lines of every token row: keep them on one XCD
     const int n_tiles = gridDim.x;
@@ -236,16 +305,31 @@ spu_fft16q(const T* __restrict__ x, int N, int D, int64_t row_stride, int sigma,
         ph[kb] = 0;                                        // (k * n2) mod N, likewise
         F[kb] = {0.f, 0.f};
     }
-    // W_N^{+-k n2} for bin kb of this thread: a power-of-two N takes the product modulo N directly, any
-    // other N keeps the running sum
-    auto tw_k = [&](int kb, int n2) {
+    // W_N^{+-k n2} for bin kb of this thread: a power-of-two N takes the product modulo N directly, any other N
+    // keeps a running sum.  The thinned inverse visits n2 = dec i2: its exponent k dec i2 mod N is dec times
+    // (k i2 mod N / dec), a running sum modulo N / dec of k reduced modulo N / dec (kpos is reduced in place once
+    // the forward transform is done).
+    const int ph_mod = 8 * N / dec;
+    auto tw_k = [&](int kb, int n2, auto inv) {
         int off;
         if (POW2) off = (int)__umul24((unsigned)kpos[kb], (unsigned)n2) & (8 * N - 1);
+        else if constexpr (decltype(inv)::value) {
+            off = (int)__umul24((unsigned)ph[kb], (unsigned)dec);
+            ph[kb] += kpos[kb];
+            if (ph[kb] >= ph_mod) ph[kb] -= ph_mod;
+        }
         else {
             off = ph[kb];
             ph[kb] += kpos[kb];
             if (ph[kb] >= 8 * N) ph[kb] -= 8 * N;
         }
+        return *reinterpret_cast<const float2*>(reinterpret_cast<const char*>(tw) + off);
+    };
+    // the same for any n2, from scratch (the subsequences the thinned inverse left out, if they are needed after all)
+    auto tw_any = [&](int kb, int n2) {
+        const int k1 = t + 16 * kb;
+        const unsigned k8 = 8u * (unsigned)(k1 <= sigma ? k1 : N - N1 + k1);
+        const unsigned off = POW2 ? (__umul24(k8, (unsigned)n2) & (unsigned)(8 * N - 1)) : (k8 * (unsigned)n2) % (unsigned)(8 * N);
         return *reinterpret_cast<const float2*>(reinterpret_cast<const char*>(tw) + off);
     };
 
@@ -280,6 +364,8 @@ spu_fft16q(const T* __restrict__ x, int N, int D, int64_t row_stride, int sigma,
             if (use_hamming) w = 0.54 + 0.46 * cospi(2.0 * (double)f / (double)(N - 1));
             gm[f] = (float)(w / (double)N);
         }
+        if (THIN) interp_build_taps(taps, dec, taps_h, taps_hw);
+        if (tid == 0) ill = 0;
     }
     __syncthreads();
     // W_N1^{t i}, i < 16: the twiddles between the two passes of every N1-point transform, both directions
@@ -342,7 +428,7 @@ spu_fft16q(const T* __restrict__ x, int N, int D, int64_t row_stride, int sigma,
                 ph[kb] = kpos[kb];               // (k * 1) mod N for the next subsequence
             }
             else {
-                const float2 w = tw_k(kb, n2);
+                const float2 w = tw_k(kb, n2, std::false_type{});
                 F[kb] = F[kb] + cmulc(u[kb], cf{w.x, w.y});    // * W_N^{k n2}
             }
         }
@@ -358,18 +444,31 @@ spu_fft16q(const T* __restrict__ x, int N, int D, int64_t row_stride, int sigma,
         const float g = (lo || hi) ? gm[lo ? k1 : N1 - k1] : 0.f;
         F[kb] = {F[kb].x * g, F[kb].y * g};
         ph[kb] = 0;
+        if (THIN && !POW2)
+            while (kpos[kb] >= ph_mod) kpos[kb] -= ph_mod;         // at most dec - 1 rounds
     }
     // ------------------------------------------------------------------ inverse (Eq. 7) and energy (Eq. 8)
-    auto inverse = [&](int n2, auto first) {
+    // (`rest`: one of the subsequences the thinned pass left out - its twiddles are worked out from scratch)
+    auto inverse = [&](int n2, auto first, bool rest) {
         cf u[Q];
+        if constexpr (decltype(first)::value) {
 #pragma unroll
-        for (int kb = 0; kb < Q; ++kb) {
-            if constexpr (decltype(first)::value) {
+            for (int kb = 0; kb < Q; ++kb) {
                 u[kb] = F[kb];
-                ph[kb] = kpos[kb];
+                ph[kb] = kpos[kb];               // phase of the next subsequence of the thinned pass
             }
-            else {
-                const float2 w = tw_k(kb, n2);
+        }
+        else if (rest) {
+#pragma unroll
+            for (int kb = 0; kb < Q; ++kb) {
+                const float2 w = tw_any(kb, n2);
+                u[kb] = cmul(F[kb], cf{w.x, w.y});
+            }
+        }
+        else {
+#pragma unroll
+            for (int kb = 0; kb < Q; ++kb) {
+                const float2 w = tw_k(kb, n2, std::true_type{});
                 u[kb] = cmul(F[kb], cf{w.x, w.y});   // F[k] W_N^{-k n2}
             }
         }
@@ -397,23 +496,117 @@ spu_fft16q(const T* __restrict__ x, int N, int D, int64_t row_stride, int sigma,
         }
         __syncthreads();
     };
-    inverse(0, std::true_type{});
+    // ------------------------------------------------------------------ thinned inverse: fill in, check
+    // (the exchange buffer is free between two subsequences: it holds the coarse energies in token order, with
+    // the taps_h - 1 before and the taps_h + 1 after them repeated at either end, and all N energies once filled in)
+    const int N2c = N2 / dec, Ns = N / dec;
+    float* ec = reinterpret_cast<float*>(xbuf);                   // [Ns + 2 taps_h + 2]: ec[i] = e[dec ((i - taps_h + 1) mod Ns)]
+    float* efull = ec + Ns + 2 * taps_h + 2;                      // [N]
+    auto fill_in = [&]() {
+        const int H = taps_h;
+        for (int i = tid; i < Ns + 2 * H + 2; i += 256) {
+            int m = i - H + 1;                   // 2 H <= Ns: one wrap at most
+            m = m < 0 ? m + Ns : (m >= Ns ? m - Ns : m);
+            const int i2 = POW2 ? (m & (N2c - 1)) : m % N2c, q = (m - i2) / N2c;       // token dec m = N2 q + dec i2
+            const int tq = Q == 16 ? (q & 15) : q % Q, j = Q == 16 ? (q >> 4) : q / Q;
+            ec[i] = eperm[(i2 * dec * Q + tq) * 16 + j];
+        }
+        __syncthreads();
+        // The tap of phase s at index i (coarse token p - H + 1 + i) is h(s / dec - (i - H + 1)) with h even, so the
+        // taps of phase dec - s are those of phase s in reverse; and h takes the sign of sinc: with H even, a tap is
+        // positive at odd i in the lower half of the window and at even i in the upper half, negative (or zero)
+        // elsewhere.  A pair (k, 2 H - 1 - k) therefore has one sign - negative for even k, positive for odd k - and
+        // the sums over even and over odd k are the negative and the positive part of e^[n]: their difference is a[n].
+        // A thread takes two neighbouring coarse tokens A = pp, B = pp + 1, whose windows differ by one entry: the
+        // loop is bound by what it reads from LDS: the energies stay fp32 there and are widened in registers (kept as
+        // doubles in LDS, the same loop was measured 5 % of the kernel slower); taps are broadcast reads.
+        bool bad = false;
+        auto emit = [&](float* dst, double pos, double neg) {
+            const double v = pos + neg;
+            bad |= v < kCondition * (pos - neg);
+            *dst = (float)v;
+        };
+        for (int pp = 2 * tid; pp < Ns; pp += 512) {
+            const float* w = ec + pp;            // w[i]: e at coarse token pp - H + 1 + i; A reads w[i], B reads w[i + 1]
+            float* out = efull + dec * pp;
+            out[0] = w[H - 1];
+            out[dec] = w[H];
+            for (int s = 1; 2 * s <= dec; ++s) {
+                const double* tp = taps + (s - 1) * 2 * H;
+                if (2 * s == dec) {              // its own mirror image: the window folds
+                    double nA = 0.0, pA = 0.0, nB = 0.0, pB = 0.0;
+#pragma unroll 2
+                    for (int k = 0; k < H; k += 2) {
+                        const double t0 = tp[k], t1 = tp[k + 1];
+                        const double a0 = (double)w[k], a1 = (double)w[k + 1], a2 = (double)w[k + 2];
+                        const double b0 = (double)w[2 * H - k], b1 = (double)w[2 * H - 1 - k], b2 = (double)w[2 * H - 2 - k];
+                        nA = fma(t0, a0 + b1, nA);
+                        pA = fma(t1, a1 + b2, pA);
+                        nB = fma(t0, a1 + b0, nB);
+                        pB = fma(t1, a2 + b1, pB);
+                    }
+                    emit(out + s, pA, nA);
+                    emit(out + dec + s, pB, nB);
+                }
+                else {                           // phases s and dec - s share the taps
+                    double nAs = 0.0, pAs = 0.0, nAd = 0.0, pAd = 0.0, nBs = 0.0, pBs = 0.0, nBd = 0.0, pBd = 0.0;
+#pragma unroll 2
+                    for (int k = 0; k < H; k += 2) {
+                        const double t0 = tp[k], u0 = tp[2 * H - 1 - k], t1 = tp[k + 1], u1 = tp[2 * H - 2 - k];
+                        const double a0 = (double)w[k], a1 = (double)w[k + 1], a2 = (double)w[k + 2];
+                        const double b0 = (double)w[2 * H - k], b1 = (double)w[2 * H - 1 - k], b2 = (double)w[2 * H - 2 - k];
+                        nAs = fma(t0, a0, fma(u0, b1, nAs));
+                        nAd = fma(t0, b1, fma(u0, a0, nAd));
+                        pAs = fma(t1, a1, fma(u1, b2, pAs));
+                        pAd = fma(t1, b2, fma(u1, a1, pAd));
+                        nBs = fma(t0, a1, fma(u0, b0, nBs));
+                        nBd = fma(t0, b0, fma(u0, a1, nBd));
+                        pBs = fma(t1, a2, fma(u1, b1, pBs));
+                        pBd = fma(t1, b1, fma(u1, a2, pBd));
+                    }
+                    emit(out + s, pAs, nAs);
+                    emit(out + dec - s, pAd, nAd);
+                    emit(out + dec + s, pBs, nBs);
+                    emit(out + 2 * dec - s, pBd, nBd);
+                }
+            }
+        }
+        if (bad) ill = 1;
+        __syncthreads();
+    };
+    inverse(0, std::true_type{}, false);
     tiles_claim<4>(sy, b, tile, n_tiles, seen);
-    for (int n2 = 1; n2 < N2; ++n2) inverse(n2, std::false_type{});
+    bool thin = THIN;                            // the energies are known at the tokens n = dec m only
+    for (int it = 1; it < N2; ++it) {
+        if (THIN && it == N2c) {                 // the thinned pass is complete
+            fill_in();
+            if (!ill) break;
+            thin = false;                        // some token cannot be trusted: the remaining subsequences after all
+        }
+        const bool rest = THIN && it >= N2c;
+        int n2 = it * dec;
+        if (rest) { const int r = it - N2c; n2 = r + r / (dec - 1) + 1; }       // the r-th n2 that dec does not divide
+        inverse(n2, std::false_type{}, rest);
+    }
     float* pout = partial + ((int64_t)b * n_tiles + tile) * N;
-    for (int n = tid; n < N; n += 256) {         // n = N2 (Q j + t') + n2
-        const int n2 = POW2 ? (n & (N2 - 1)) : n % N2;
-        const int q = (n - n2) / N2;
-        const int tq = Q == 16 ? (q & 15) : q % Q, j = Q == 16 ? (q >> 4) : q / Q;
-        tile_store(pout + n, eperm[(n2 * Q + tq) * 16 + j]);
+    if (THIN && thin) {
+        for (int n = tid; n < N; n += 256) tile_store(pout + n, efull[n]);
+    }
+    else {
+        for (int n = tid; n < N; n += 256) {     // n = N2 (Q j + t') + n2
+            const int n2 = POW2 ? (n & (N2 - 1)) : n % N2;
+            const int q = (n - n2) / N2;
+            const int tq = Q == 16 ? (q & 15) : q % Q, j = Q == 16 ? (q >> 4) : q / Q;
+            tile_store(pout + n, eperm[(n2 * Q + tq) * 16 + j]);
+        }
     }
     // ------------------------------------------------------------------ Eq. 8 across the channel tiles
     tiles_to_scores<256, 4>(partial, gpartial, sy, scores, b, tile, n_tiles, N, &is_last);
 }
 
-static size_t fft_lds_bytes(int N, int Q, int sigma)
+static size_t fft_lds_bytes(int N, int Q, int sigma, int n_taps)
 {
-    return sizeof(float2) * (size_t)(16 * kRowPad + N + 16 * Q) + sizeof(float) * (size_t)(N + sigma + 1);
+    return sizeof(float2) * (size_t)(16 * kRowPad + N + 16 * Q) + sizeof(float) * (size_t)((N + sigma + 1 + 1) / 2 * 2) + sizeof(double) * (size_t)n_taps;
 }
 
 // the residue-side length Q of the 16 x Q transform that serves (N, sigma); 0 if none does
@@ -429,18 +622,45 @@ static int fft_pick_q(int N, int sigma)
 
 bool spu_fft_supported(int N, int sigma) { return fft_pick_q(N, sigma) != 0; }
 
+// How far the inverse is thinned out: the divisor dec of N2 that saves the most, counting a subsequence of the
+// inverse at its ~630 vector instructions per wavefront and a tap of the fill-in at 6 (two LDS reads, four fp64
+// operations) per coarse token and phase; 1 if nothing saves a fifth of the inverse or fits.
+struct ThinPlan { int dec, taps_h; double taps_hw; };
+static ThinPlan fft_thin_plan(int N, int Q, int sigma)
+{
+    ThinPlan best{1, 0, 0.0};
+    const int N2 = N / (16 * Q);
+    double best_gain = 0.2 * 630.0 * N2;
+    for (int dec = 2; dec <= N2; ++dec) {
+        if (N2 % dec) continue;
+        const int Ns = N / dec;
+        const double hw = interp_half_width(Ns, sigma);
+        if (hw <= 0.0) continue;
+        const int H = interp_taps_half(hw);
+        if (2 * H > Ns || (dec - 1) * 2 * H > kMaxTaps) continue;
+        if (sizeof(float) * (size_t)(Ns + 2 * H + 2 + N) > sizeof(float2) * (size_t)(16 * kRowPad)) continue;
+        const double gain = 630.0 * (N2 - N2 / dec) - 6.0 * (dec - 1) * 2 * H * ((Ns + 255) / 256);
+        if (gain > best_gain) { best_gain = gain; best = ThinPlan{dec, H, hw}; }
+    }
+    return best;
+}
+
 luvc_status spu_score_fft(const void* x, int B, int N, int D, int64_t row_stride, luvc_dtype dt, int sigma, int use_hamming,
                           float* partial, float* gpartial, const TileSync& sy, int n_tiles, float* scores, hipStream_t st)
 {
     const int Q = fft_pick_q(N, sigma);
-    const size_t lds = fft_lds_bytes(N, Q, sigma);
+    const ThinPlan tp = fft_thin_plan(N, Q, sigma);
+    const int dec = tp.dec, taps_h = tp.taps_h;
+    const double taps_hw = tp.taps_hw;
+    const size_t lds = fft_lds_bytes(N, Q, sigma, (dec - 1) * 2 * taps_h);
     const bool pow2 = (N & (N - 1)) == 0;
     // channel pairs are fetched with one access when every pair is naturally aligned
     const size_t es = dt == LUVC_F32 ? 4 : 2;
     const bool aligned = (row_stride % 2 == 0) && ((uintptr_t)x % (2 * es) == 0) && (D % 2 == 0);
     if (n_tiles > 65535) { set_error("D=%d exceeds the supported width of the fft path", D); return LUVC_ERR_UNSUPPORTED; }
     const dim3 grid((unsigned)n_tiles, (unsigned)B);
-#define LUVC_FFT(TT, QQ, P2, AL) LUVC_LAUNCH("spu_fft16q", (spu_fft16q<TT, QQ, P2, AL>), grid, dim3(256), lds, st, (const TT*)x, N, D, row_stride, sigma, use_hamming, partial, gpartial, sy, scores)
+#define LUVC_FFT_H(TT, QQ, P2, AL, TH) LUVC_LAUNCH("spu_fft16q", (spu_fft16q<TT, QQ, P2, AL, TH>), grid, dim3(256), lds, st, (const TT*)x, N, D, row_stride, sigma, use_hamming, dec, taps_h, taps_hw, partial, gpartial, sy, scores)
+#define LUVC_FFT(TT, QQ, P2, AL) do { if (dec > 1) LUVC_FFT_H(TT, QQ, P2, AL, true); else LUVC_FFT_H(TT, QQ, P2, AL, false); } while (0)
 #define LUVC_FFT_A(TT, QQ, P2) do { if (aligned) LUVC_FFT(TT, QQ, P2, true); else LUVC_FFT(TT, QQ, P2, false); } while (0)
 #define LUVC_FFT_T(TT) do { if (Q == 16) { if (pow2) LUVC_FFT_A(TT, 16, true); else LUVC_FFT_A(TT, 16, false); } \
                             else if (Q == 15) LUVC_FFT_A(TT, 15, false); else LUVC_FFT_A(TT, 9, false); } while (0)
@@ -448,6 +668,7 @@ luvc_status spu_score_fft(const void* x, int B, int N, int D, int64_t row_stride
 #undef LUVC_FFT_T
 #undef LUVC_FFT_A
 #undef LUVC_FFT
+#undef LUVC_FFT_H
     return check_launch("spu score (fft)");
 }
 

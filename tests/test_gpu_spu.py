@@ -269,3 +269,28 @@ def test_calls_from_several_host_threads():
     for th in threads:
         th.join()
     assert not errors, errors
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("B,N,D,sigma", [(2, 1024, 96, 102), (1, 2048, 64, 102), (1, 768, 64, 50), (1, 1008, 64, 7), (1, 960, 40, 20)])
+def test_score_where_token_energies_vanish(oracle, dtype, B, N, D, sigma):
+    """Lengths on which the fft path evaluates the inverse on a subset of the tokens and fills in the rest from the
+    band limit of the tile energies - which is ill-conditioned wherever a token's filtered channels all but vanish
+    next to neighbours whose channels do not.  The kernel must notice (per tile) and evaluate those tiles in full:
+    the bar is the same 1e-5 as everywhere."""
+    rng = np.random.default_rng(N + D + sigma)
+    n = np.arange(N)
+    gains = rng.standard_normal(D)
+    f = max(1, sigma // 2)
+    tone = np.cos(2 * np.pi * f * n / N + 0.3)[None, :, None] * gains[None, None, :]           # every channel crosses zero at the same tokens
+    x = np.broadcast_to(tone, (B, N, D)).astype(np.float32)
+    score_case(oracle, wl.cast_io(x, dtype), dtype, sigma, True, "tone")
+    x = rng.standard_normal((B, N, D)).astype(np.float32)
+    x[:, N // 3: N // 3 + N // 5] = 0.0                                                         # a span of padding tokens
+    score_case(oracle, wl.cast_io(x, dtype), dtype, sigma, True, "padding")
+    x = rng.standard_normal((B, N, D)).astype(np.float32)
+    x[:, :, :32] = tone[:, :, :32]                                                              # one ill-conditioned tile among ordinary ones
+    score_case(oracle, wl.cast_io(x, dtype), dtype, sigma, False, "one-tile")
+    x = np.zeros((B, N, D), np.float32)
+    x[:, N // 2, :] = 1.0                                                                       # an impulse: the filter's own kernel, with its side-lobe zeros
+    score_case(oracle, wl.cast_io(x, dtype), dtype, sigma, True, "impulse")
