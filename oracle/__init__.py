@@ -23,7 +23,10 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "luvc_oracle.c")
-_LIB = os.path.join(_HERE, "libluvc_oracle.so")
+# LUVC_ORACLE_SANITIZE=1 selects a build with AddressSanitizer and UndefinedBehaviorSanitizer (its own file, so the
+# ordinary build is left alone); the process then needs gcc's libasan.so preloaded, see README.
+_SANITIZE = os.environ.get("LUVC_ORACLE_SANITIZE", "") not in ("", "0")
+_LIB = os.path.join(_HERE, "libluvc_oracle_san.so" if _SANITIZE else "libluvc_oracle.so")
 
 ROUND_NONE, ROUND_F32, ROUND_BF16 = 0, 1, 2
 
@@ -31,8 +34,9 @@ ROUND_NONE, ROUND_F32, ROUND_BF16 = 0, 1, 2
 def build(force: bool = True) -> str:
     """Compile the oracle with gcc (``-O2``, OpenMP over independent images/samples)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        opt = ["-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined", "-fno-omit-frame-pointer"] if _SANITIZE else ["-O2"]
         subprocess.check_call(
-            ["gcc", "-O2", "-fopenmp", "-std=c99", "-D_GNU_SOURCE", "-shared", "-fPIC", "-Wall",
+            ["gcc", *opt, "-fopenmp", "-std=c99", "-D_GNU_SOURCE", "-shared", "-fPIC", "-Wall",
              "-o", _LIB, _SRC, "-lm"])
     return _LIB
 

@@ -11,7 +11,8 @@ import os
 from typing import List, Optional, Sequence, Tuple
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libluvc.so")
+# LUVC_HOST_SANITIZE=1 loads the build whose host code carries the sanitizers (see build.py)
+LIB_PATH = os.path.join(_HERE, "libluvc_san.so" if os.environ.get("LUVC_HOST_SANITIZE", "") not in ("", "0") else "libluvc.so")
 
 LUVC_OK, LUVC_ERR_INVALID_ARG, LUVC_ERR_UNSUPPORTED, LUVC_ERR_WORKSPACE, LUVC_ERR_HIP = range(5)
 LUVC_F32, LUVC_BF16 = 0, 1

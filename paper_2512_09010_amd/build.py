@@ -9,8 +9,13 @@ from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
-LIB = os.path.join(HERE, "libluvc.so")
-OBJ = os.path.join(HERE, "_build")
+# LUVC_HOST_SANITIZE=1: the host half of the library (argument checks, planners, ragged batching) is built with
+# AddressSanitizer and UndefinedBehaviorSanitizer into a file of its own; device code is unchanged.  The process that
+# loads it needs clang's libclang_rt.asan-x86_64.so preloaded, see README.
+SANITIZE = os.environ.get("LUVC_HOST_SANITIZE", "") not in ("", "0")
+LIB = os.path.join(HERE, "libluvc_san.so" if SANITIZE else "libluvc.so")
+OBJ = os.path.join(HERE, "_build_san" if SANITIZE else "_build")
+SAN_FLAGS = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host", "-fno-omit-frame-pointer", "-g"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -40,7 +45,7 @@ def build(force: bool = True, verbose: bool = False) -> str:
 
     def compile_one(src):
         obj = os.path.join(OBJ, os.path.basename(src) + ".o")
-        cmd = [HIPCC, *FLAGS, *os.environ.get("LUVC_HIPCC_EXTRA", "").split(), "-c", src, "-o", obj]
+        cmd = [HIPCC, *FLAGS, *(SAN_FLAGS if SANITIZE else []), *os.environ.get("LUVC_HIPCC_EXTRA", "").split(), "-c", src, "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         r = subprocess.run(cmd, capture_output=True, text=True)
@@ -54,7 +59,7 @@ def build(force: bool = True, verbose: bool = False) -> str:
 
     with ThreadPoolExecutor(max_workers=min(8, len(srcs))) as ex:
         objs = list(ex.map(compile_one, srcs))
-    subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB])
+    subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *(["-fsanitize=address", "-fsanitize=undefined", "-shared-libsan"] if SANITIZE else []), *objs, "-o", LIB])
     return LIB
 
 
