@@ -329,6 +329,16 @@ luvc_status luvc_profile_start(void** hip_events, int n_events);
 int luvc_profile_stop(void);
 const char* luvc_profile_kernel(int i);
 
+/*
+ * Self-test aid (not a step of the paper's method): the fp32 sums the OIM screening forms with the packed bf16 dot
+ * product instruction, exposed so that a test can hold them against exact sums - the error bound the screening relies
+ * on (Section 3.2 decisions are fp64 decisions; fp32 only screens them) counts one rounding per product pair and one
+ * per accumulation.
+ *   x, y      device [rows, 2 * words] bf16: row r holds `words` pairs of elements
+ *   out       device [rows] fp32: out[r] = the instruction applied to the pairs of row r in order, starting from 0
+ */
+luvc_status luvc_selftest_fdot2(const void* x, const void* y, int rows, int words, float* out, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -23,7 +23,7 @@ EXPORTS = ("luvc_version", "luvc_last_error", "luvc_oim_plan", "luvc_oim_workspa
            "luvc_spu_cascade_keeps", "luvc_spu_stage",
            "luvc_oim_plan_anyres", "luvc_oim_ragged_workspace_bytes", "luvc_oim_merge_ragged",
            "luvc_spu_ragged_workspace_bytes", "luvc_spu_stage_ragged",
-           "luvc_profile_start", "luvc_profile_stop", "luvc_profile_kernel")
+           "luvc_profile_start", "luvc_profile_stop", "luvc_profile_kernel", "luvc_selftest_fdot2")
 
 
 class LuvcPass(ctypes.Structure):
@@ -99,6 +99,8 @@ def lib() -> ctypes.CDLL:
     L.luvc_profile_stop.restype = i
     L.luvc_profile_kernel.argtypes = [i]
     L.luvc_profile_kernel.restype = ctypes.c_char_p
+    L.luvc_selftest_fdot2.argtypes = [vp, vp, i, i, vp, vp]
+    L.luvc_selftest_fdot2.restype = i
     _lib = L
     return L
 
@@ -472,3 +474,13 @@ class LaunchProfile:
             if self.events[k]:
                 self._hip.hipEventDestroy(self.events[k])
                 self.events[k] = None
+
+
+def luvc_selftest_fdot2(x, y, stream=None):
+    """x, y [rows, 2 * words] bf16 -> [rows] fp32: the packed bf16 dot product instruction chained over a row."""
+    import torch
+    assert x.is_cuda and x.dtype == torch.bfloat16 and x.shape == y.shape and x.dim() == 2 and x.shape[1] % 2 == 0
+    assert x.is_contiguous() and y.is_contiguous()
+    out = torch.empty((x.shape[0],), dtype=torch.float32, device=x.device)
+    _check(lib().luvc_selftest_fdot2(_ptr(x), _ptr(y), x.shape[0], x.shape[1] // 2, _ptr(out), _stream(stream)))
+    return out

@@ -281,3 +281,34 @@ luvc_status oim_halve_pass(const void* x, const int32_t* sizes_in, int B, int H,
 }
 
 }  // namespace luvc
+
+// ------------------------------------------------------------------ self-test aid
+namespace luvc {
+__global__ void __launch_bounds__(256)
+selftest_fdot2(const uint32_t* __restrict__ x, const uint32_t* __restrict__ y, int rows, int nwords, float* __restrict__ out)
+{
+    const int r = blockIdx.x * blockDim.x + threadIdx.x;
+    if (r >= rows) return;
+    float acc = 0.f;
+    for (int i = 0; i < nwords; ++i) {
+        bf16x2_t a, b;
+        const uint32_t xa = x[(int64_t)r * nwords + i], yb = y[(int64_t)r * nwords + i];
+        __builtin_memcpy(&a, &xa, 4);
+        __builtin_memcpy(&b, &yb, 4);
+        acc = __builtin_amdgcn_fdot2_f32_bf16(a, b, acc, false);
+    }
+    out[r] = acc;
+}
+}  // namespace luvc
+
+extern "C" luvc_status luvc_selftest_fdot2(const void* x, const void* y, int rows, int words, float* out, void* hip_stream)
+{
+    using namespace luvc;
+    if (!x || !y || !out || rows < 1 || words < 1 || ((uintptr_t)x | (uintptr_t)y | (uintptr_t)out) % 4) {
+        set_error("luvc_selftest_fdot2: null or misaligned pointer, or rows / words < 1");
+        return LUVC_ERR_INVALID_ARG;
+    }
+    LUVC_LAUNCH("selftest_fdot2", selftest_fdot2, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, (hipStream_t)hip_stream,
+                (const uint32_t*)x, (const uint32_t*)y, rows, words, out);
+    return check_launch("selftest fdot2");
+}

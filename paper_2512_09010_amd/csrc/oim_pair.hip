@@ -287,8 +287,15 @@ __device__ __forceinline__ void chain_sums64(Tok<NQ, TW>& P0, Tok<NQ, TW>& P1, T
     d[0] = dot64<T>(P0, P1); d[1] = dot64<T>(P1, P2); d[2] = dot64<T>(P2, P3); d[3] = dot64<T>(P3, P4);
 }
 
-// 1 / max(|x|, 1e-12) from the squared norm, screening precision (hardware reciprocal square root)
-__device__ __forceinline__ float inv_norm32(float n2) { return n2 < 1e-24f ? 1e12f : __builtin_amdgcn_rsqf(n2); }
+// 1 / |x| from the squared norm, screening precision (hardware reciprocal square root) - or NaN, which makes the
+// screening abstain (the fp64 values decide), when the squared norm lies outside [2^-60, 2^100]: the error bound of
+// the screening counts relative roundings only, and those are all there is inside that window (terms that the
+// packed bf16 dot product flushes to zero are below 2^-126 each, 2^-54 of such a norm at most; nothing overflows).
+// Zero and near-zero tokens, for which the cosine is defined through the 1e-12 clamp, go to fp64 the same way.
+__device__ __forceinline__ float inv_norm32(float n2)
+{
+    return (n2 >= 8.6736174e-19f && n2 <= 1.2676506e30f) ? __builtin_amdgcn_rsqf(n2) : __builtin_nanf("");
+}
 
 __device__ __forceinline__ double inv_norm64(double n2)
 {
@@ -441,7 +448,9 @@ oim_halve_pair(const T* __restrict__ x, const int32_t* __restrict__ sizes_in, Pa
     // per packed bf16 product pair, one per fp32 product; six reduction steps); against |a||b| that is E u
     // on a dot product and E u on each squared norm, i.e. (E + 4) u on the two reciprocal norms together
     // (hardware reciprocal square root: 1 ulp each), plus two products: 2 E + 6 per cosine, 4 E + 13 on
-    // the difference of two.  tau is 1.5 times that.
+    // the difference of two.  tau is 1.5 times that.  Each step of the packed bf16 dot product is taken as one or two
+    // roundings to nearest of the exact value (tests/test_gpu_oim.py pins the instruction's sums against fp64);
+    // underflow and overflow are kept out by inv_norm32().
     constexpr int kE = N * (words<T>::per == 2 ? 2 : 1) + 6;
     const float tau = (float)(6 * kE + 20) * 5.9604645e-8f;
     const int tok_bytes = g.D * (int)sizeof(T);

@@ -129,10 +129,13 @@ __device__ __forceinline__ float wave_sum32(float v)
     return v;
 }
 
+// 1 / |x| for the screening - or NaN, which makes the screening abstain (the fp64 values decide), when the squared
+// norm lies outside [2^-60, 2^100]: inside that window the fp32 sums neither lose terms to underflow (the packed bf16
+// dot product flushes products below 2^-126: 2^-54 of such a norm at most) nor overflow, which is what the error
+// bound behind tau assumes.  Zero and near-zero tokens (cosine defined through the 1e-12 clamp) go to fp64 as well.
 __device__ __forceinline__ float inv_norm32(float n2)
 {
-    const float n = sqrtf(n2);
-    return 1.0f / (n < 1e-12f ? 1e-12f : n);
+    return (n2 >= 8.6736174e-19f && n2 <= 1.2676506e30f) ? 1.0f / sqrtf(n2) : __builtin_nanf("");
 }
 
 // Screening verdict for one source: +1 = left for certain, -1 = right for certain, 0 = too close to call

@@ -21,7 +21,7 @@ def L():
 def declared_symbols():
     text = open(os.path.join(ROOT, "include", "luvc.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(luvc_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(luvc_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_exports_match_header(L):

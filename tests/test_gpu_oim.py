@@ -263,3 +263,43 @@ def test_decisions_closer_than_the_arithmetic_resolves(oracle, dtype):
         run_case(oracle, x_io, dtype, passes, tag="scaled copies")
         margins.append(oracle.oim_merge(wl.widen(x_io, dtype), passes, round_mode=round_mode(oracle, dtype))["margin"])
     assert min(margins) <= OIM_MARGIN                                       # the case does visit the situation it is written for
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("exp2", [-63, -40, 55, 63])
+def test_extreme_magnitudes(oracle, dtype, exp2):
+    """Features scaled by 2^-63 (~1e-19), 2^-40, 2^55 and 2^63 (~1e19): fp32 squared norms underflow, lose terms or
+    overflow there, so the fp32 screening must abstain and the fp64 values decide - through the fused pair kernel,
+    the single halving pass and the general path (m = 2)."""
+    rng = np.random.default_rng(1000 + exp2)
+    x = (rng.standard_normal((2, 8, 10, 96)) * 2.0 ** exp2).astype(np.float32)
+    x_io = wl.cast_io(x, dtype)
+    for passes in (_halving(8, 10, "WH"), _halving(8, 10, "HW"), [(W_AX, 5)], [(H_AX, 4)], [(W_AX, 2), (H_AX, 2)]):
+        run_case(oracle, x_io, dtype, passes, tag=f"scaled 2^{exp2}")
+    # one image of ordinary magnitude beside a tiny and a huge one, and zero tokens in between
+    y = rng.standard_normal((3, 8, 10, 96)).astype(np.float32)
+    y[1] *= 2.0 ** exp2
+    y[2, :, 3:5] = 0.0
+    run_case(oracle, wl.cast_io(y, dtype), dtype, _halving(8, 10, "WH"), tag=f"mixed 2^{exp2}")
+
+
+def test_packed_bf16_dot_rounds_like_the_screening_bound_assumes():
+    """The error bound of the fp32 screening takes every step acc <- acc + x0 y0 + x1 y1 of the packed bf16 dot product
+    as at most two roundings to nearest (relative 2^-24 each) of partial sums bounded by the sum of the magnitudes of
+    the terms.  Held here against exact sums (fp64 is exact for products of bf16 values and sums of 40 of them over
+    this range) on random rows, rows with cancellation and rows of one sign."""
+    rng = np.random.default_rng(5)
+    rows, words = 4096, 20
+    xs = [rng.standard_normal((rows, 2 * words)), np.abs(rng.standard_normal((rows, 2 * words))),
+          rng.standard_normal((rows, 2 * words)) * np.exp2(rng.integers(-8, 8, (rows, 2 * words)))]
+    ys = [rng.standard_normal((rows, 2 * words)), np.abs(rng.standard_normal((rows, 2 * words))),
+          rng.standard_normal((rows, 2 * words))]
+    for x, y in zip(xs, ys):
+        xb, yb = wl.cast_io(x.astype(np.float32), "bf16"), wl.cast_io(y.astype(np.float32), "bf16")
+        got = lv.luvc_selftest_fdot2(to_dev(xb, "bf16"), to_dev(yb, "bf16")).cpu().numpy().astype(np.float64)
+        xe, ye = wl.widen(xb, "bf16"), wl.widen(yb, "bf16")
+        exact = (xe * ye).sum(axis=1)
+        mag = np.abs(xe * ye).sum(axis=1)
+        bound = 2 * words * 2.0 ** -24 * mag
+        assert (np.abs(got - exact) <= bound).all(), float((np.abs(got - exact) / bound).max())
+        print(f"[fdot2] worst error / bound = {float((np.abs(got - exact) / bound).max()):.3f}", flush=True)
