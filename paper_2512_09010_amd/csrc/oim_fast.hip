@@ -230,8 +230,7 @@ static void launch_halve(const T* x, const int32_t* sizes_in, int B, int H, int 
                          hipStream_t st)
 {
     const int len = axis ? W : H, nlines = axis ? H : W, nd = len / 2;
-    static const int tune = getenv("LUVC_OIM_SPT") ? atoi(getenv("LUVC_OIM_SPT")) : 4;   // tuning knob, 1..8
-    const int cap = tune < 1 ? 1 : (tune > 8 ? 8 : tune);
+    constexpr int cap = 4;
     const int spt = nd < cap ? nd : cap;                   // wavefronts (= output slots) per workgroup
     const int tiles = (nd + spt - 1) / spt;
     LUVC_LAUNCH("oim_halve", (oim_halve<T, NCH>), dim3((unsigned)((int64_t)B * nlines * tiles)), dim3(64 * spt), 0, st,

@@ -79,9 +79,7 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t token_rsrc(const void* p, int 
 
 // cache policy of token loads (buffer aux bits): default, because the neighbouring workgroups read the same tokens
 // again from L2 (the non-temporal hint was measured slower: 36.3 against 34.9 us on 8 x 64 x 64 x 1280 bf16)
-#ifndef LUVC_OIM_LOAD_AUX
-#define LUVC_OIM_LOAD_AUX 0
-#endif
+constexpr int kLoadAux = 0;
 // a token that is not there (past the end of the line) is a zero-length buffer: every lane reads zeros
 template <int NQ, int TW>
 __device__ __forceinline__ void load_tok(Tok<NQ, TW>& t, const void* p, int bytes, int lane, bool present = true)
@@ -89,21 +87,19 @@ __device__ __forceinline__ void load_tok(Tok<NQ, TW>& t, const void* p, int byte
     const __amdgpu_buffer_rsrc_t rsrc = token_rsrc(p, present ? bytes : 0);
 #pragma unroll
     for (int q = 0; q < NQ; ++q) {
-        const u32x4 r = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (q * 64 + lane) * 16, 0, LUVC_OIM_LOAD_AUX);
+        const u32x4 r = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (q * 64 + lane) * 16, 0, kLoadAux);
         t.w[4 * q] = r[0]; t.w[4 * q + 1] = r[1]; t.w[4 * q + 2] = r[2]; t.w[4 * q + 3] = r[3];
     }
-    if (TW == 1) t.w[4 * NQ] = __builtin_amdgcn_raw_buffer_load_b32(rsrc, NQ * 1024 + lane * 4, 0, LUVC_OIM_LOAD_AUX);
+    if (TW == 1) t.w[4 * NQ] = __builtin_amdgcn_raw_buffer_load_b32(rsrc, NQ * 1024 + lane * 4, 0, kLoadAux);
     if (TW == 2) {
-        const u32x2 r = __builtin_amdgcn_raw_buffer_load_b64(rsrc, NQ * 1024 + lane * 8, 0, LUVC_OIM_LOAD_AUX);
+        const u32x2 r = __builtin_amdgcn_raw_buffer_load_b64(rsrc, NQ * 1024 + lane * 8, 0, kLoadAux);
         t.w[4 * NQ] = r[0]; t.w[4 * NQ + 1] = r[1];
     }
 }
 
 // output tokens are not read again by this kernel: non-temporal stores (2) leave less dirty data in L2 for the end of
 // the kernel (measured: 36.2 -> 34.9 us, and a shorter gap to the next launch)
-#ifndef LUVC_OIM_STORE_AUX
-#define LUVC_OIM_STORE_AUX 2
-#endif
+constexpr int kStoreAux = 2;
 template <int NQ, int TW>
 __device__ __forceinline__ void store_tok(void* p, int bytes, const Tok<NQ, TW>& t, int lane)
 {
@@ -112,13 +108,13 @@ __device__ __forceinline__ void store_tok(void* p, int bytes, const Tok<NQ, TW>&
     for (int q = 0; q < NQ; ++q) {
         u32x4 r;
         r[0] = t.w[4 * q]; r[1] = t.w[4 * q + 1]; r[2] = t.w[4 * q + 2]; r[3] = t.w[4 * q + 3];
-        __builtin_amdgcn_raw_buffer_store_b128(r, rsrc, (q * 64 + lane) * 16, 0, LUVC_OIM_STORE_AUX);
+        __builtin_amdgcn_raw_buffer_store_b128(r, rsrc, (q * 64 + lane) * 16, 0, kStoreAux);
     }
-    if (TW == 1) __builtin_amdgcn_raw_buffer_store_b32(t.w[4 * NQ], rsrc, NQ * 1024 + lane * 4, 0, LUVC_OIM_STORE_AUX);
+    if (TW == 1) __builtin_amdgcn_raw_buffer_store_b32(t.w[4 * NQ], rsrc, NQ * 1024 + lane * 4, 0, kStoreAux);
     if (TW == 2) {
         u32x2 r;
         r[0] = t.w[4 * NQ]; r[1] = t.w[4 * NQ + 1];
-        __builtin_amdgcn_raw_buffer_store_b64(r, rsrc, NQ * 1024 + lane * 8, 0, LUVC_OIM_STORE_AUX);
+        __builtin_amdgcn_raw_buffer_store_b64(r, rsrc, NQ * 1024 + lane * 8, 0, kStoreAux);
     }
 }
 
@@ -466,10 +462,7 @@ oim_halve_pair(const T* __restrict__ x, const int32_t* __restrict__ sizes_in, Pa
     unsigned took_a = 0, took_c = 0;                              // bit k: row k absorbed its a / its c
     // the four rows unrolled: the compiler renames T0..T3 instead of moving 10 registers per token and row
     // (measured: 35.3 -> 34.2 us on 8 x 64 x 64 x 1280 bf16)
-#ifndef LUVC_OIM_UNROLL
-#define LUVC_OIM_UNROLL 4
-#endif
-#pragma unroll LUVC_OIM_UNROLL
+#pragma unroll 4
     for (int k = 0; k < 4; ++k) {
         const int r = r0 + k;
         TokT Tn;
@@ -653,11 +646,10 @@ PairPlan plan_pair(int L2, int nw, int64_t lines)
 {
     const int nd2 = L2 / 2;
     PairPlan p;
-    static const int env_forced = getenv("LUVC_OIM_SEG") ? atoi(getenv("LUVC_OIM_SEG")) : 0;   // tuning knob: outputs per workgroup
     // A grid with fewer line positions than the chip has CUs would leave most of it idle with one workgroup
     // per position: cut the lines into runs of 8 outputs then (measured on 2 x 112 x 112, 56 x 56 and
     // 28 x 28 grids: 64 us for the three calls against 78; runs of 2, 6 or 14 gain less).
-    const int forced = env_forced > 0 ? env_forced : ((lines < 256 && nd2 > 8) ? 8 : 0);
+    const int forced = (lines < 256 && nd2 > 8) ? 8 : 0;
     if ((L2 + 3) / 4 <= nw && forced <= 0) {
         p.segs = 1;
         p.seg_out = nd2;
@@ -733,8 +725,7 @@ luvc_status dispatch_pair(const T* x, const int32_t* sizes_in, int B, int H, int
 
 bool oim_pair_supported(int H, int W, int D, luvc_dtype dt, int axis0, int m0, int axis1, int m1, bool vec)
 {
-    static const bool off = getenv("LUVC_OIM_NO_PAIR") != nullptr;   // tuning knob: force one launch per pass
-    if (off || !vec || axis0 == axis1) return false;
+    if (!vec || axis0 == axis1) return false;
     const int len0 = axis0 ? W : H, len1 = axis1 ? W : H;           // the second pass runs on the untouched axis
     if (len0 < 2 || len1 < 2 || m0 != (len0 + 1) / 2 || m1 != (len1 + 1) / 2) return false;
     return (int64_t)D * (dt == LUVC_F32 ? 4 : 2) <= 4096;

@@ -256,11 +256,8 @@ __device__ __forceinline__ void interp_build_taps(double* taps, int dec, int H, 
 
 }  // namespace
 
-#ifndef LUVC_FFT_WAVES
-#define LUVC_FFT_WAVES 2
-#endif
 template <typename T, int Q, bool POW2, bool ALIGNED, bool THIN>
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((Q == 9 || (Q == 15 && sizeof(T) == 2)) ? 3 : LUVC_FFT_WAVES)))
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((Q == 9 || (Q == 15 && sizeof(T) == 2)) ? 3 : 2)))
 spu_fft16q(const T* __restrict__ x, int N, int D, int64_t row_stride, int sigma, int use_hamming,
            int dec_arg /* THIN: the inverse starts with the subsequences n2 = 0, dec, 2 dec, ... */, int taps_h, double taps_hw,
            float* __restrict__ partial /* [B, n_tiles, N] */, float* __restrict__ gpartial /* [B, n_groups, N] */,
@@ -369,10 +366,7 @@ spu_fft16q(const T* __restrict__ x, int N, int D, int64_t row_stride, int sigma,
     }
     __syncthreads();
     // W_N1^{t i}, i < 16: the twiddles between the two passes of every N1-point transform, both directions
-#ifndef LUVC_FFT_HOIST
-#define LUVC_FFT_HOIST 1
-#endif
-    constexpr bool kHoist = LUVC_FFT_HOIST == 2 || (LUVC_FFT_HOIST == 1 && Q == 16);
+    constexpr bool kHoist = Q == 16;
     cf w1[16];
     if (kHoist) {
         int e1 = 0;

@@ -168,12 +168,7 @@ spu_gather(const unsigned char* __restrict__ x, const int32_t* __restrict__ kept
 // wait between the two, which is most of the time at these sizes.
 // cache policy of the row copies (buffer aux bits): the copied rows are not read again by this kernel, so the stores
 // carry the non-temporal hint (2) and leave less dirty data in L2 for the end of the kernel (measured: -0.3 us)
-#ifndef LUVC_PRUNE_LD_AUX
-#define LUVC_PRUNE_LD_AUX 0
-#endif
-#ifndef LUVC_PRUNE_ST_AUX
-#define LUVC_PRUNE_ST_AUX 2
-#endif
+constexpr int kPruneLoadAux = 0, kPruneStoreAux = 2;
 typedef unsigned int prune_u32x4 __attribute__((__vector_size__(16)));
 constexpr int kFusedMaxN = 4096, kFusedThreads = 256, kFusedKeys = kFusedMaxN / kFusedThreads;
 
@@ -278,9 +273,9 @@ spu_prune_fused(const unsigned char* __restrict__ x, const float* __restrict__ s
             for (int base = 0; base < rb; base += 8 * 1024) {
                 prune_u32x4 v[8];
 #pragma unroll
-                for (int k = 0; k < 8; ++k) v[k] = __builtin_amdgcn_raw_buffer_load_b128(ri, base + k * 1024 + lane * 16, 0, LUVC_PRUNE_LD_AUX);
+                for (int k = 0; k < 8; ++k) v[k] = __builtin_amdgcn_raw_buffer_load_b128(ri, base + k * 1024 + lane * 16, 0, kPruneLoadAux);
 #pragma unroll
-                for (int k = 0; k < 8; ++k) __builtin_amdgcn_raw_buffer_store_b128(v[k], ro, base + k * 1024 + lane * 16, 0, LUVC_PRUNE_ST_AUX);
+                for (int k = 0; k < 8; ++k) __builtin_amdgcn_raw_buffer_store_b128(v[k], ro, base + k * 1024 + lane * 16, 0, kPruneStoreAux);
             }
         } else if (BYTES == 4) {
             for (int64_t i = (int64_t)lane * 4; i < row_bytes_out; i += 64 * 4)

@@ -175,16 +175,8 @@ static size_t dense_fused_lds(int N, int sigma)
 }
 
 // LDS a workgroup of the one-launch kernel may take (of the 160 KB of a compute unit; above 64 KB one workgroup
-// per compute unit is resident).  LUVC_SPU_DENSE_LDS_KB overrides it for measurements.
-static size_t dense_fused_cap()
-{
-    static const size_t cap = [] {
-        const char* e = getenv("LUVC_SPU_DENSE_LDS_KB");
-        const long kb = e ? atol(e) : 144;
-        return (size_t)(kb < 0 ? 0 : kb > 144 ? 144 : kb) * 1024;
-    }();
-    return cap;
-}
+// per compute unit is resident)
+static size_t dense_fused_cap() { return (size_t)144 * 1024; }
 
 template <typename T>
 __global__ void __launch_bounds__(64 * kDfWaves)
