@@ -24,11 +24,19 @@
 // 4 sigma) fix all N of them.  The inverse therefore runs on every dec-th subsequence first; the workgroup fills
 // in the tokens between with a Kaiser-windowed sinc (fp64 taps and sums; cut-off half the coarse rate, stop band
 // 140 dB down: design error 1e-7 of the energies around the token) and checks, token by token, that the value it
-// got is not small against the absolute sum  a[n] = sum |tap| e[m]  it came from: e^[n] >= a[n] / 32.  Rounding
-// errors of the e[m] (relative 2e-7 at most) reach e^[n] multiplied by at most a[n] / e^[n], so a tile that
-// passes hands over energies that are within 1e-5 of what the full inverse gives, and the sum over tiles
-// inherits the bound.  A tile with a token that fails (a token whose filtered channels all but vanish where its
-// neighbours' do not) runs the remaining subsequences and hands over what Eq. 7-8 say, as if dec were 1.
+// got is not small against the absolute sum  a[n] = sum |tap| e[m]  it came from: e^[n] >= a[n] / 8.  The fp32
+// transform leaves an absolute error of about eps x_rms on every filtered value, whatever its size, hence
+// 2 sqrt(e[m]) eps x_rms on an energy; a filled-in energy collects sum |tap| times that, and the score, its square
+// root, (sum |tap| sqrt(e[m])) / sqrt(e[n]) times the error the full inverse would leave on it.  The check keeps the
+// energies around a filled-in token within about three times its own (the taps sum to about 2.5 in absolute value),
+// so that factor stays below five: a tile that passes hands over scores whose error is a few 1e-7 of the sample's
+// largest score at worst, next to the 1e-7 of the full inverse.  The design error of the kernel is of another
+// kind: what the window cuts off the sinc only cancels for a band-limited sequence as a whole, so the error is
+// about 2e-7 of the LARGEST energy anywhere near, not of the token's own - a filled-in token must therefore also
+// reach 1/32 of the tile's largest coarse energy (then the design error is below 7e-6 of its energy, 3.2e-6 of its
+// score).  The sum over tiles inherits both bounds.  A tile with a token that fails either test (a token whose
+// filtered channels all but vanish where others' do not) runs the remaining subsequences and hands over what
+// Eq. 7-8 say, as if dec were 1.
 #include <type_traits>
 
 #include "common.hpp"
@@ -189,6 +197,16 @@ template <> struct pair_io<float> {
 constexpr int kPairs = 16;                       // channel pairs per workgroup
 constexpr int kRowPad = 16 * kPairs + kPairs;    // float2 per exchange row: 16 x 16 pairs + one pad group
 
+// largest value over the 16 lanes of a DPP row, in every lane of the row
+__device__ __forceinline__ float row16_max(float v)
+{
+    v = fmaxf(v, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xf, 0xf, false)));
+    v = fmaxf(v, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x4E, 0xf, 0xf, false)));
+    v = fmaxf(v, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x141, 0xf, 0xf, false)));
+    v = fmaxf(v, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x140, 0xf, 0xf, false)));
+    return v;
+}
+
 // sum over the 16 lanes of a DPP row; every lane of the row ends up with the total, fixed order
 __device__ __forceinline__ float row16_sum(float v)
 {
@@ -225,7 +243,8 @@ __device__ __forceinline__ double bessel_i0(double x)
 constexpr double kKaiserAtten = 140.0;                           // dB
 constexpr double kKaiserBeta = 0.1102 * (kKaiserAtten - 8.7);    // 14.5
 constexpr double kPi = 3.14159265358979323846;
-constexpr double kCondition = 1.0 / 32.0;                        // a tile is interpolated only if e^[n] >= kCondition * a[n] for all n
+constexpr double kCondition = 1.0 / 8.0;                         // a tile is filled in only if e^[n] >= kCondition * a[n] ...
+constexpr double kFloorShare = 1.0 / 32.0;                       // ... and e^[n] >= kFloorShare * (largest coarse energy of the tile), for all n
 constexpr int kMaxTaps = 256;                                    // (dec - 1) * 2 H, doubles in LDS
 
 // Half-width (in coarse samples) of the kernel for Ns samples of a polynomial of degree <= 2 sigma: the transition
@@ -274,6 +293,7 @@ spu_fft16q(const T* __restrict__ x, int N, int D, int64_t row_stride, int sigma,
     float* gm = eperm + N;                       // [sigma + 1]  M[f] / N  (Eq. 5 with the 1/N of Eq. 7)
     double* taps = reinterpret_cast<double*>(smem + 16 * kRowPad + N + N1) + (N + sigma + 1 + 1) / 2;    // [(dec - 1) 2 H]
     __shared__ int is_last, ill;                 // ill: some token of the tile cannot be interpolated
+    __shared__ float emax_w[4];                  // largest coarse energy of the tile, per wavefront
     const int tid = threadIdx.x, c = tid & 15, t = tid >> 4;
     // neighbouring channel tiles share 128-byte lines of every token row: keep them on one XCD
     const int n_tiles = gridDim.x;
@@ -498,14 +518,23 @@ spu_fft16q(const T* __restrict__ x, int N, int D, int64_t row_stride, int sigma,
     float* efull = ec + Ns + 2 * taps_h + 2;                      // [N]
     auto fill_in = [&]() {
         const int H = taps_h;
+        float big = 0.f;
         for (int i = tid; i < Ns + 2 * H + 2; i += 256) {
             int m = i - H + 1;                   // 2 H <= Ns: one wrap at most
             m = m < 0 ? m + Ns : (m >= Ns ? m - Ns : m);
             const int i2 = POW2 ? (m & (N2c - 1)) : m % N2c, q = (m - i2) / N2c;       // token dec m = N2 q + dec i2
             const int tq = Q == 16 ? (q & 15) : q % Q, j = Q == 16 ? (q >> 4) : q / Q;
-            ec[i] = eperm[(i2 * dec * Q + tq) * 16 + j];
+            const float v = eperm[(i2 * dec * Q + tq) * 16 + j];
+            ec[i] = v;
+            big = fmaxf(big, v);
         }
+        auto rl = [](float v, int l) { return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), l)); };
+        big = row16_max(big);
+        big = fmaxf(fmaxf(rl(big, 0), rl(big, 16)),
+                    fmaxf(rl(big, 32), rl(big, 48)));
+        if ((tid & 63) == 0) emax_w[tid >> 6] = big;
         __syncthreads();
+        const double emax_share = kFloorShare * (double)fmaxf(fmaxf(emax_w[0], emax_w[1]), fmaxf(emax_w[2], emax_w[3]));
         // The tap of phase s at index i (coarse token p - H + 1 + i) is h(s / dec - (i - H + 1)) with h even, so the
         // taps of phase dec - s are those of phase s in reverse; and h takes the sign of sinc: with H even, a tap is
         // positive at odd i in the lower half of the window and at even i in the upper half, negative (or zero)
@@ -517,7 +546,7 @@ spu_fft16q(const T* __restrict__ x, int N, int D, int64_t row_stride, int sigma,
         bool bad = false;
         auto emit = [&](float* dst, double pos, double neg) {
             const double v = pos + neg;
-            bad |= v < kCondition * (pos - neg);
+            bad |= v < kCondition * (pos - neg) || v < emax_share;
             *dst = (float)v;
         };
         for (int pp = 2 * tid; pp < Ns; pp += 512) {

@@ -360,9 +360,15 @@ spu_dense_fused(const T* __restrict__ x, int N, int D, int64_t row_stride, int s
 tile_tag_t spu_next_tag()
 {
     static std::atomic<unsigned long long> next{[] {
-        std::random_device rd;
+        unsigned long long r = 0;
+        try {
+            std::random_device rd;
+            r = ((unsigned long long)rd() << 32) ^ (unsigned long long)rd();
+        } catch (...) {                                    // no entropy source: the clock and an address will have to do
+            r = (unsigned long long)(uintptr_t)&r;
+        }
         const unsigned long long t = (unsigned long long)std::chrono::steady_clock::now().time_since_epoch().count();
-        return (((unsigned long long)rd() << 32) ^ (unsigned long long)rd() ^ (t * 0x9E3779B97F4A7C15ull));
+        return r ^ (t * 0x9E3779B97F4A7C15ull);
     }()};
     for (;;) {
         const tile_tag_t tag = next.fetch_add(1, std::memory_order_relaxed) & 0xffffffffffffull;
