@@ -294,3 +294,34 @@ def test_score_where_token_energies_vanish(oracle, dtype, B, N, D, sigma):
     x = np.zeros((B, N, D), np.float32)
     x[:, N // 2, :] = 1.0                                                                       # an impulse: the filter's own kernel, with its side-lobe zeros
     score_case(oracle, wl.cast_io(x, dtype), dtype, sigma, True, "impulse")
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_score_fuzz_on_lengths_with_a_thinned_inverse(oracle, seed):
+    """Seeded random cases on the lengths the fft path serves, mostly with bands narrow enough for the thinned inverse:
+    white noise, tones that cross zero in every channel, spans of zero tokens, a few dominant channels, token norms
+    that swing over orders of magnitude, random walks (large energies next to small ones across the wrap-around)."""
+    rng = np.random.default_rng(900 + seed)
+    lengths = [512, 768, 1024, 1280, 1536, 2048, 3072, 4096, 480, 960, 1440, 1200, 288, 432, 576, 1008, 720, 2304]
+    for it in range(25):
+        N = int(rng.choice(lengths))
+        dtype = "bf16" if rng.integers(2) else "f32"
+        B, D = int(rng.integers(1, 4)), int(rng.choice([2, 31, 32, 33, 64, 96, 130, 257]))
+        q = 16 if N % 256 == 0 else (15 if N % 240 == 0 else 9)
+        smax = min((16 * q - 1) // 2, N // 2)
+        sigma = int(rng.integers(0, max(1, min(smax, N // 8)) + 1)) if rng.integers(4) else int(rng.integers(0, smax + 1))
+        kind = int(rng.integers(6))
+        n = np.arange(N)
+        x = rng.standard_normal((B, N, D))
+        if kind == 1:
+            x = np.cos(2 * np.pi * max(1, sigma // 2) * n / N + rng.uniform(0, 6))[None, :, None] * rng.standard_normal(D)[None, None, :] + 1e-3 * x
+        if kind == 2:
+            x[:, rng.integers(0, N // 2): rng.integers(N // 2, N)] = 0
+        if kind == 3:
+            x = x * np.exp(rng.standard_normal((1, 1, D)) * 3)
+        if kind == 4:
+            x = x * (np.abs(np.sin(2 * np.pi * 3 * n / N)) ** 4)[None, :, None]
+        if kind == 5:
+            x = np.cumsum(x, axis=1) / np.sqrt(N)
+        pad = int(rng.choice([0, 0, 3, 8]))
+        score_case(oracle, wl.cast_io(x.astype(np.float32), dtype), dtype, sigma, True, f"thin-fuzz{seed}.{it} kind={kind}", stride_pad=pad)
