@@ -176,6 +176,11 @@ size_t luvc_spu_workspace_bytes(int B, int N, int D, luvc_dtype dtype, int sigma
  *   scores      device [B,N] fp32
  * Arithmetic is fp32 (bf16 is a storage type only).  The sum over channels is taken in a fixed order:
  * the same input gives the same bits on every call.
+ * Accuracy: within 1e-5 relative of Eq. 4-8 evaluated exactly, plus 1e-6 of the sample's largest score for tokens
+ * whose filtered energy all but vanishes.  For lengths N = 16 Q N2 (Q = 16, 15, 9) with 2 sigma + 1 <= 16 Q and
+ * N / dec > 4 sigma for a divisor dec of N2, Eq. 7 is evaluated on every dec-th token and the energies between are
+ * filled in from the band limit 2 sigma of the energy sequence, 32 channels at a time, wherever two conditioning
+ * tests show that this stays inside the same bounds; elsewhere Eq. 7 is evaluated on every token.
  * Concurrency: calls may overlap on different streams, or with replays of a captured graph, as long as each call
  * in flight has its own workspace.  The workspace may hold anything when the call starts (the completion counters
  * the single-launch kernels keep in it recognise stale contents), and nothing in it is needed afterwards.
