@@ -314,7 +314,8 @@ luvc_status luvc_oim_merge_wide(const void* x, const int32_t* sizes_in, int B, i
                           workspace, workspace_bytes, hip_stream);
 }
 
-// ---- OIM decided on a separate metric tensor (general kernels only: decisions and merge are separate stages)
+// ---- OIM decided on a separate metric tensor: a pair of halving passes is one launch (oim_pair_keyed.hip), any other pass
+// runs its decisions and its two merges (features, metric) as separate stages on the general kernels
 struct KeyedLayout {
     OimLayout base;
     size_t mbuf[2], bytes;          // ping-pong buffers of the merged metric between passes
@@ -327,9 +328,11 @@ static KeyedLayout keyed_layout(int B, int D, int Dm, luvc_dtype dt, const OimPl
     K.base = oim_layout(B, D, dt, pl, passes, radius);
     size_t off = K.base.bytes;
     size_t tok[2] = {0, 0};
-    for (int i = 0; i < pl.n; ++i) {              // the metric of the last pass may be wanted as well (metric_out == NULL)
+    // launch s (one pass, or two passes fused) writes buffer s & 1; which passes fuse depends on the alignment of the
+    // caller's buffers, so both hold the largest grid any pass writes (the last one too: metric_out may be NULL)
+    for (int i = 0; i < pl.n; ++i) {
         const size_t t = (size_t)B * pl.h[i + 1] * pl.w[i + 1];
-        if (t > tok[i & 1]) tok[i & 1] = t;
+        if (t > tok[0]) tok[0] = tok[1] = t;
     }
     for (int j = 0; j < 2; ++j) { K.mbuf[j] = off; off += align_up(tok[j] * Dm * esize(dt)); }
     K.bytes = off;
@@ -396,36 +399,52 @@ luvc_status luvc_oim_merge_keyed(const void* x, const void* metric, const int32_
     const void *cur_x = x, *cur_m = metric;
     const int32_t* cur_s = sizes_in;
     const int32_t* cur_k = nullptr;
+    // launches of the call: a pair of halving passes on different axes with adjacent matching runs as one launch
+    struct Step { int first, count; };
+    Step steps[kMaxPasses];
+    int n_steps = 0;
+    for (int i = 0; i < pl.n;) {
+        const bool pair = radius == 1 && i + 1 < pl.n &&
+                          oim_pair_keyed_supported(pl.h[i], pl.w[i], D, Dm, dtype, passes[i].axis, passes[i].m, passes[i + 1].axis, passes[i + 1].m, vec_x, vec_m);
+        steps[n_steps++] = Step{i, pair ? 2 : 1};
+        i += pair ? 2 : 1;
+    }
     const int32_t* maps[kMaxPasses];
     int32_t n_in[kMaxPasses];
-    for (int i = 0; i < pl.n; ++i) {
-        const bool last = i + 1 == pl.n;
+    for (int s = 0; s < n_steps; ++s) {
+        const int i = steps[s].first, e = i + steps[s].count - 1;          // passes i..e
+        const bool last = e + 1 == pl.n;
         const int h = pl.h[i], w = pl.w[i], axis = passes[i].axis, m = passes[i].m;
-        void* ox = last ? x_out : (void*)(ws + L.xbuf[i & 1]);
-        void* om = (last && metric_out) ? metric_out : (void*)(ws + K.mbuf[i & 1]);
-        int32_t* os = last ? sizes_out : (int32_t*)(ws + L.sbuf[i & 1]);
-        int32_t* ok = last ? kept_map : (int32_t*)(ws + L.kbuf[i & 1]);
-        int32_t* pm = (pl.n == 1 && merged_map) ? merged_map : (int32_t*)(ws + L.maps[i]);
-        maps[i] = pm;
-        n_in[i] = h * w;
+        void* ox = last ? x_out : (void*)(ws + L.xbuf[s & 1]);
+        void* om = (last && metric_out) ? metric_out : (void*)(ws + K.mbuf[s & 1]);
+        int32_t* os = last ? sizes_out : (int32_t*)(ws + L.sbuf[s & 1]);
+        int32_t* ok = last ? kept_map : (int32_t*)(ws + L.kbuf[s & 1]);
+        int32_t* pm = (n_steps == 1 && merged_map) ? merged_map : (int32_t*)(ws + L.maps[i]);
+        maps[s] = pm;
+        n_in[s] = h * w;
         luvc_status rc;
-        if (radius == 1) rc = oim_general_decide(cur_m, B, h, w, Dm, dtype, axis, m, vec_m, pm, sc, st);
-        else             rc = oim_wide_decide(cur_m, B, h, w, Dm, dtype, axis, m, radius, vec_m, pm, sc, G, src_dest, st);
-        if (rc != LUVC_OK) return rc;
-        if (radius == 1) rc = oim_general_apply(cur_x, cur_s, B, h, w, D, dtype, axis, m, vec_x, ox, os, cur_k, ok, sc, st);
-        else             rc = oim_wide_apply(cur_x, cur_s, B, h, w, D, dtype, axis, m, vec_x, ox, os, cur_k, ok, sc, src_dest, st);
-        if (rc != LUVC_OK) return rc;
-        if (!last || metric_out) {               // the metric follows its own decisions (sizes and anchors are written again, same values)
-            if (radius == 1) rc = oim_general_apply(cur_m, cur_s, B, h, w, Dm, dtype, axis, m, vec_m, om, os, nullptr, nullptr, sc, st);
-            else             rc = oim_wide_apply(cur_m, cur_s, B, h, w, Dm, dtype, axis, m, vec_m, om, os, nullptr, nullptr, sc, src_dest, st);
+        if (steps[s].count == 2) {
+            rc = oim_pair_keyed_pass(cur_x, cur_m, cur_s, B, h, w, D, Dm, dtype, axis, ox, (last && !metric_out) ? nullptr : om, os, pm, cur_k, ok, st);
             if (rc != LUVC_OK) return rc;
+        } else {
+            if (radius == 1) rc = oim_general_decide(cur_m, B, h, w, Dm, dtype, axis, m, vec_m, pm, sc, st);
+            else             rc = oim_wide_decide(cur_m, B, h, w, Dm, dtype, axis, m, radius, vec_m, pm, sc, G, src_dest, st);
+            if (rc != LUVC_OK) return rc;
+            if (radius == 1) rc = oim_general_apply(cur_x, cur_s, B, h, w, D, dtype, axis, m, vec_x, ox, os, cur_k, ok, sc, st);
+            else             rc = oim_wide_apply(cur_x, cur_s, B, h, w, D, dtype, axis, m, vec_x, ox, os, cur_k, ok, sc, src_dest, st);
+            if (rc != LUVC_OK) return rc;
+            if (!last || metric_out) {               // the metric follows its own decisions (sizes and anchors are written again, same values)
+                if (radius == 1) rc = oim_general_apply(cur_m, cur_s, B, h, w, Dm, dtype, axis, m, vec_m, om, os, nullptr, nullptr, sc, st);
+                else             rc = oim_wide_apply(cur_m, cur_s, B, h, w, Dm, dtype, axis, m, vec_m, om, os, nullptr, nullptr, sc, src_dest, st);
+                if (rc != LUVC_OK) return rc;
+            }
         }
         cur_x = ox;
         cur_m = om;
         cur_s = os;
         cur_k = ok;
     }
-    if (merged_map && pl.n > 1) return oim_compose(maps, n_in, pl.n, B, H * W, merged_map, st);
+    if (merged_map && n_steps > 1) return oim_compose(maps, n_in, n_steps, B, H * W, merged_map, st);
     return LUVC_OK;
 }
 

@@ -63,6 +63,13 @@ luvc_status oim_pair_pass(const void* x, const int32_t* sizes_in, int B, int H, 
                           void* x_out, int32_t* sizes_out, int32_t* pair_map, const int32_t* kept_prev, int32_t* kept_out,
                           hipStream_t st);
 
+// The same pair of passes decided on a metric tensor of Dm values per token (oim_pair_keyed.hip): features and
+// metric are merged alike; metric_out may be NULL when the merged metric is not wanted.
+bool oim_pair_keyed_supported(int H, int W, int D, int Dm, luvc_dtype dt, int axis0, int m0, int axis1, int m1, bool vec_x, bool vec_m);
+luvc_status oim_pair_keyed_pass(const void* x, const void* metric, const int32_t* sizes_in, int B, int H, int W, int D, int Dm,
+                                luvc_dtype dt, int first_axis, void* x_out, void* metric_out, int32_t* sizes_out, int32_t* pair_map,
+                                const int32_t* kept_prev, int32_t* kept_out, hipStream_t st);
+
 luvc_status oim_compose(const int32_t* const* maps, const int32_t* n_in, int n, int B, int n_first,
                         int32_t* merged_out, hipStream_t st);
 

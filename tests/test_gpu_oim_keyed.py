@@ -73,6 +73,91 @@ def test_keyed_without_metric_output(oracle):
     np.testing.assert_array_equal(to_host_f64(out["x"]), ref["x"])
 
 
+def _halving(H, W, order):
+    passes = []
+    for ax in order:
+        if ax == "W":
+            passes.append((W_AX, (W + 1) // 2)); W -= (W + 1) // 2
+        else:
+            passes.append((H_AX, (H + 1) // 2)); H -= (H + 1) // 2
+    return passes
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("B,H,W,D,Dm,order", [
+    (2, 2, 2, 16, 8, "WH"),            # smallest pair
+    (2, 8, 8, 64, 32, "WH"),
+    (2, 8, 8, 64, 128, "HW"),          # Algorithm 1 order: height first; keys wider than the tokens
+    (1, 9, 7, 40, 24, "WH"),           # odd lengths on both axes
+    (1, 7, 9, 40, 24, "HW"),
+    (1, 3, 2, 24, 16, "WH"),
+    (2, 12, 10, 520, 72, "WH"),        # ragged last piece of a token and of a key
+    (1, 70, 6, 48, 16, "WH"),          # second-pass lines cut into runs: rows outside a run are looked at for decisions only
+    (1, 6, 70, 48, 136, "HW"),
+    (1, 131, 4, 32, 64, "WH"),         # three runs, odd length
+    (1, 24, 24, 1280, 128, "WH"),      # the token width of the batch workloads, keys of one attention head
+    (1, 12, 12, 2048, 256, "HW"),      # largest token, eight wavefronts per workgroup
+    (1, 12, 12, 640, 512, "WH"),       # largest key in bf16 (1 KB); in fp32 it is beyond the fused kernel: general kernels
+    (1, 16, 16, 72, 40, "WHWH"),       # two pairs in one call: maps compose, the second pair decides on the merged keys
+    (1, 16, 16, 72, 40, "WHW"),        # a pair followed by a single pass on the general kernels
+    (2, 32, 24, 72, 40, "WWHW"),       # single, pair, single: intermediates alternate per launch
+])
+def test_keyed_halving_pairs(oracle, dtype, B, H, W, D, Dm, order):
+    rng = np.random.default_rng(B * 1000 + H * 100 + W * 10 + D + Dm + len(order))
+    x = wl.cast_io(rng.standard_normal((B, H, W, D)).astype(np.float32), dtype)
+    keys = wl.cast_io(wl.smooth_field(rng, B, H, W, Dm, 2.0) + 0.1 * rng.standard_normal((B, H, W, Dm)).astype(np.float32), dtype)
+    passes = _halving(H, W, order)
+    run_keyed(oracle, x, keys, dtype, passes, 1, tag="pair smooth keys")
+    sizes = rng.integers(1, 6, (B, H, W))
+    run_keyed(oracle, x, keys, dtype, passes, 1, sizes=sizes, tag="pair smooth keys+sizes")
+    kr = wl.cast_io(rng.standard_normal((B, H, W, Dm)).astype(np.float32), dtype)
+    run_keyed(oracle, x, kr, dtype, passes, 1, sizes=sizes, tag="pair random keys+sizes")
+
+
+def test_keyed_pair_with_the_tokens_as_keys_is_the_plain_call():
+    # both kernels decide on fp64 cosines (the plain one wherever its fp32 screening is unsure); their sums run in
+    # different orders, which only a decision closer than 1e-15 could notice - these inputs have none
+    rng = np.random.default_rng(19)
+    for (B, H, W, D, order) in ((2, 16, 16, 128, "WH"), (1, 70, 10, 256, "HW"), (1, 13, 11, 512, "WHWH")):
+        x = to_dev(wl.cast_io(wl.smooth_field(rng, B, H, W, D, 2.0) + 0.1 * rng.standard_normal((B, H, W, D)).astype(np.float32), "bf16"), "bf16")
+        passes = _halving(H, W, order)
+        a = lv.luvc_oim_merge_keyed(x, x, passes, 1)
+        b = lv.luvc_oim_merge(x, passes)
+        torch.cuda.synchronize()
+        for k in ("x", "sizes", "merged_map", "kept_map"):
+            assert torch.equal(a[k], b[k]), (H, W, D, order, k)
+        assert torch.equal(a["metric"], a["x"])
+
+
+def test_keyed_pair_close_calls_and_degenerate_keys(oracle):
+    # near-duplicate keys (cosines closer than fp32 resolves), rows and columns of identical keys (ties go to the
+    # lower position), zero keys (cosine through the norm clamp)
+    rng = np.random.default_rng(23)
+    base = rng.standard_normal((1, 1, 1, 64)).astype(np.float32)
+    keys = base + 1e-3 * rng.standard_normal((2, 12, 12, 64)).astype(np.float32)
+    keys[0, 3] = keys[0, 3, 0]
+    keys[1, :, 5] = keys[1, 0, 5]
+    keys[1, 7, 2:6] = 0.0
+    x = rng.standard_normal((2, 12, 12, 96)).astype(np.float32)
+    for dtype in ("bf16", "f32"):
+        for order in ("WH", "HW"):
+            run_keyed(oracle, wl.cast_io(x, dtype), wl.cast_io(keys, dtype), dtype, _halving(12, 12, order), 1, tag="close calls " + order)
+
+
+def test_keyed_pair_without_metric_and_maps(oracle):
+    rng = np.random.default_rng(29)
+    x = wl.cast_io(rng.standard_normal((2, 10, 12, 64)).astype(np.float32), "bf16")
+    keys = wl.cast_io(rng.standard_normal((2, 10, 12, 32)).astype(np.float32), "bf16")
+    passes = _halving(10, 12, "HW")
+    ref = oracle.oim_merge_keyed(wl.widen(x, "bf16"), wl.widen(keys, "bf16"), passes, R=1, round_mode=oracle.ROUND_BF16)
+    assert ref["margin"] > OIM_MARGIN
+    out = lv.luvc_oim_merge_keyed(to_dev(x, "bf16"), to_dev(keys, "bf16"), passes, 1, want_metric=False, want_maps=False)
+    torch.cuda.synchronize()
+    assert out["metric"] is None
+    np.testing.assert_array_equal(to_host_f64(out["x"]), ref["x"])
+    np.testing.assert_array_equal(out["sizes"].cpu().numpy().astype(np.int64), ref["sizes"])
+
+
 @pytest.mark.parametrize("dtype,shape", [("f32", (3, 7, 33)), ("bf16", (2, 64, 1280)), ("bf16", (5, 3, 10)), ("f32", (1, 19, 256))])
 def test_value_enhance(oracle, dtype, shape):
     rng = np.random.default_rng(sum(shape))
