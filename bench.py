@@ -380,11 +380,13 @@ def oim_wide_leg(lv, torch, w, xs_oim, n_rot, tdt, code, es, stream, steps):
         ln, nl = (W, H) if axis else (H, W)
         flops += 2.0 * w.grids * nl * ((ln + 1) // 2) * (ln // 2) * w.D
         H, W = (H, W - m) if axis else (H - m, W)
-    g = float(np.sum(per.get("oim_line_gram", [0.0]))) / n_prof
+    # the contraction runs inside oim_wide_line (one launch per pass) or, for lines beyond its limit, as oim_line_gram
+    gk = "oim_wide_line" if "oim_wide_line" in per else "oim_line_gram"
+    g = float(np.sum(per.get(gk, [0.0]))) / n_prof
     kernels = {k: {"launches_per_call": len(v) / n_prof, "avg_us": round(float(np.mean(v)) * 1e3, 2)} for k, v in per.items()}
     return {"what": "whole-line matching (radius 0), m = 2, passes (W,2),(H,2) x 3", "ms_per_call": round(ms, 5),
             "tokens_per_s": round(w.tokens_in / (ms * 1e-3), 1), "kernels": kernels,
-            "roofline": {"kernel": "oim_line_gram", "bound": "mfma", "dtype": "f64", "achieved": round(flops / (g * 1e-3) / 1e12, 2) if g else None,
+            "roofline": {"kernel": gk, "bound": "mfma", "dtype": "f64", "achieved": round(flops / (g * 1e-3) / 1e12, 2) if g else None,
                          "peak": 78.6, "unit": "TFLOP/s", "frac": round(flops / (g * 1e-3) / 1e12 / 78.6, 4) if g else None,
                          "algorithmic_flops_per_call": int(flops)}}
 

@@ -80,7 +80,8 @@ static bool walk_schedule(int B, int H, int W, int D, const luvc_oim_pass* passe
 }
 
 struct OimLayout {
-    size_t xbuf[2], sbuf[2], kbuf[2], maps[kMaxPasses], n2, dn, anchor, absorb, gram, srcdest, bytes;
+    size_t xbuf[2], sbuf[2], kbuf[2], maps[kMaxPasses], n2, dn, anchor, absorb, gram, srcdest, lazy_idx[2], lazy_ov, bytes;
+    int lazy_cap;      // overlay rows per image (wide matching with one launch per pass)
 };
 
 static OimLayout oim_layout(int B, int D, luvc_dtype dt, const OimPlan& pl, const luvc_oim_pass* passes = nullptr, int radius = 1)
@@ -120,6 +121,17 @@ static OimLayout oim_layout(int B, int D, luvc_dtype dt, const OimPlan& pl, cons
         }
     L.gram = off;    off += align_up(gram);
     L.srcdest = off; off += align_up(srcdest);
+    // wide matching with one launch per pass: two grids of row ids and the rows of the merged destinations
+    // (whether a call can run that way depends on the alignment of its buffers, so the space is always there)
+    int64_t cap = 0;
+    if (radius != 1 && passes)
+        for (int i = 0; i < pl.n; ++i) cap += oim_wide_lazy_rows(pl.h[i], pl.w[i], passes[i].axis, passes[i].m);
+    L.lazy_cap = (int)cap;
+    for (int j = 0; j < 2; ++j) {
+        L.lazy_idx[j] = off;
+        off += (radius != 1 && passes) ? align_up((size_t)B * pl.h[0] * pl.w[0] * sizeof(int32_t)) : 0;
+    }
+    L.lazy_ov = off; off += align_up((size_t)B * (size_t)cap * D * esize(dt));
     L.bytes = off;
     return L;
 }
@@ -236,6 +248,37 @@ static luvc_status oim_merge_impl(const void* x, const int32_t* sizes_in, int B,
     const size_t es = esize(dtype);
     // 16-byte accesses need aligned rows in every buffer the kernels touch
     const bool vec = ((size_t)D * es) % 16 == 0 && (uintptr_t)x % 16 == 0 && (uintptr_t)x_out % 16 == 0;
+
+    bool lazy = radius != 1 && vec && (int64_t)H * W + L.lazy_cap < ((int64_t)1 << 31);
+    for (int i = 0; i < pl.n; ++i)
+        if ((passes[i].axis ? pl.w[i] : pl.h[i]) > kLazyMaxLen) lazy = false;
+    if (lazy) {
+        // one launch per pass on grids of row ids, the tokens move once at the end
+        const int32_t *cur_i = nullptr, *cur_sz = sizes_in, *cur_kp = nullptr;
+        const int32_t* lmaps[kMaxPasses];
+        int32_t ln_in[kMaxPasses];
+        int ov_base = 0;
+        for (int i = 0; i < pl.n; ++i) {
+            const bool last = i + 1 == pl.n;
+            int32_t* oi = (int32_t*)(ws + L.lazy_idx[i & 1]);
+            int32_t* os = last ? sizes_out : (int32_t*)(ws + L.sbuf[i & 1]);
+            int32_t* ok = last ? kept_map : (int32_t*)(ws + L.kbuf[i & 1]);
+            int32_t* pm = merged_map ? ((pl.n == 1) ? merged_map : (int32_t*)(ws + L.maps[i])) : nullptr;
+            lmaps[i] = pm;
+            ln_in[i] = pl.h[i] * pl.w[i];
+            const luvc_status rc = oim_wide_lazy_pass(x, ws + L.lazy_ov, cur_i, cur_sz, cur_kp, B, H * W, pl.h[i], pl.w[i], D, dtype,
+                                                      passes[i].axis, passes[i].m, radius, L.lazy_cap, ov_base, oi, os, ok, pm, st);
+            if (rc != LUVC_OK) return rc;
+            ov_base += oim_wide_lazy_rows(pl.h[i], pl.w[i], passes[i].axis, passes[i].m);
+            cur_i = oi;
+            cur_sz = os;
+            cur_kp = ok;
+        }
+        const luvc_status rc = oim_wide_lazy_gather(x, ws + L.lazy_ov, cur_i, B, H * W, L.lazy_cap, Ho * Wo, D, dtype, x_out, st);
+        if (rc != LUVC_OK) return rc;
+        if (merged_map && pl.n > 1) return oim_compose(lmaps, ln_in, pl.n, B, H * W, merged_map, st);
+        return LUVC_OK;
+    }
 
     OimScratch sc;
     sc.n2 = (double*)(ws + L.n2);

@@ -34,6 +34,17 @@ luvc_status oim_wide_pass(const void* x, const int32_t* sizes_in, int B, int H, 
                           const int32_t* kept_prev, int32_t* kept_out,
                           const OimScratch& ws, double* G, int32_t* src_dest, hipStream_t st);
 
+// Wide matching with one launch per pass and the tokens moved once, at the end (oim_wide_lazy.hip): grids between the
+// passes are tensors of row ids (below n0: a token of x; from n0: a row of the overlay `ov`, which receives the merged
+// destinations).  Lines of at most kLazyMaxLen tokens, 16-byte aligned rows.
+constexpr int kLazyMaxLen = 128;
+int oim_wide_lazy_rows(int h, int w, int axis, int m);      // overlay rows per image that a pass may write
+luvc_status oim_wide_lazy_pass(const void* x, void* ov, const int32_t* idx_in, const int32_t* sizes_in, const int32_t* kept_in,
+                               int B, int n0, int h, int w, int D, luvc_dtype dt, int axis, int m, int radius, int cap, int ov_base,
+                               int32_t* idx_out, int32_t* sizes_out, int32_t* kept_out, int32_t* pass_map, hipStream_t st);
+luvc_status oim_wide_lazy_gather(const void* x, const void* ov, const int32_t* idx, int B, int n0, int cap, int n_out_per, int D,
+                                 luvc_dtype dt, void* x_out, hipStream_t st);
+
 // The two stages of a pass on their own: decisions on one tensor (`metric`), merge applied to another.
 luvc_status oim_general_decide(const void* metric, int B, int H, int W, int Dm, luvc_dtype dt, int axis, int m, bool vec,
                                int32_t* pass_map, const OimScratch& ws, hipStream_t st);

@@ -127,3 +127,53 @@ def test_wide_merge_near_a_rounding_tie(oracle):
     x_io = wl.cast_io(x, "bf16")
     run_wide(oracle, x_io, "bf16", [(H_AX, 2)], 0, sizes=sizes, tag="tie+tiny")
     run_wide(oracle, np.ascontiguousarray(x_io.transpose(0, 2, 1, 3)), "bf16", [(W_AX, 2)], 2, sizes=np.ascontiguousarray(sizes.transpose(0, 2, 1)), tag="tie+tiny W")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("B,H,W,D,passes,radius", [
+    (1, 2, 128, 16, [(W_AX, 3), (W_AX, 2)], 0),            # longest line of the one-launch passes
+    (1, 127, 2, 24, [(H_AX, 64)], 0),                      # every source merged, odd length
+    (1, 2, 140, 16, [(W_AX, 5), (H_AX, 1)], 0),            # longer lines: the three-launch passes
+    (1, 300, 1, 8, [(H_AX, 7)], 3),
+    (2, 20, 20, 64, [(W_AX, 0), (H_AX, 3), (W_AX, 10), (H_AX, 0)], 0),   # passes that merge nothing between passes that do
+])
+def test_wide_line_lengths_around_the_one_launch_limit(oracle, dtype, B, H, W, D, passes, radius):
+    rng = np.random.default_rng(H * 1000 + W + D)
+    x = wl.cast_io(wl.smooth_field(rng, B, H, W, D, 2.0) + 0.3 * rng.standard_normal((B, H, W, D)).astype(np.float32), dtype)
+    sizes = rng.integers(1, 4, (B, H, W))
+    run_wide(oracle, x, dtype, passes, radius, tag="lengths")
+    run_wide(oracle, x, dtype, passes, radius, sizes=sizes, tag="lengths+sizes")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_wide_one_launch_passes_and_three_launch_passes_agree(dtype):
+    """The same call on a 16-byte aligned input (row ids between the passes, one launch per pass, tokens moved once) and
+    on a copy that starts 8 bytes off (every pass materialised by three launches): identical outputs."""
+    rng = np.random.default_rng(31)
+    B, H, W, D = 2, 24, 20, 136
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    x = torch.from_numpy(wl.smooth_field(rng, B, H, W, D, 2.0) + 0.3 * rng.standard_normal((B, H, W, D)).astype(np.float32)).to(tdt).cuda()
+    off = 8 // x.element_size()
+    flat = torch.empty(x.numel() + off, dtype=tdt, device="cuda")
+    flat[off:] = x.reshape(-1)
+    x_off = flat[off:].view(B, H, W, D)
+    assert x.data_ptr() % 16 == 0 and x_off.data_ptr() % 16 == 8
+    sizes = torch.from_numpy(rng.integers(1, 5, (B, H, W)).astype(np.int32)).cuda()
+    for passes, radius in (([(W_AX, 2), (H_AX, 2)] * 3, 0), ([(H_AX, 5), (W_AX, 10), (H_AX, 1)], 2)):
+        a = lv.luvc_oim_merge_wide(x, passes, radius, sizes=sizes)
+        b = lv.luvc_oim_merge_wide(x_off, passes, radius, sizes=sizes)
+        torch.cuda.synchronize()
+        for k in ("x", "sizes", "merged_map", "kept_map"):
+            assert torch.equal(a[k], b[k]), (passes, radius, k)
+
+
+def test_wide_without_maps(oracle):
+    rng = np.random.default_rng(37)
+    x = wl.cast_io(rng.standard_normal((2, 10, 12, 64)).astype(np.float32), "bf16")
+    passes = [(W_AX, 2), (H_AX, 2), (W_AX, 3)]
+    ref = oracle.oim_merge(wl.widen(x, "bf16"), passes, R=0, round_mode=oracle.ROUND_BF16)
+    assert ref["margin"] > OIM_MARGIN
+    out = lv.luvc_oim_merge_wide(to_dev(x, "bf16"), passes, 0, want_maps=False)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(to_host_f64(out["x"]), ref["x"])
+    np.testing.assert_array_equal(out["sizes"].cpu().numpy().astype(np.int64), ref["sizes"])
