@@ -344,6 +344,16 @@ const char* luvc_profile_kernel(int i);
  */
 luvc_status luvc_selftest_fdot2(const void* x, const void* y, int rows, int words, float* out, void* hip_stream);
 
+/*
+ * Self-test aid (not a step of the paper's method): the 32 x 32 tile of dot products that the wide matching of
+ * luvc_oim_merge_wide forms on the matrix cores in the storage precision to screen its fp64 decisions (Section 3.2,
+ * Algorithm 1; the decisions themselves are taken on fp64 cosines), exposed so that a test can hold it against exact
+ * sums: the screening assumes |out - exact| <= D 2^-23 times the sum of the magnitudes of the products.
+ *   a, c      device [32, D] rows of `dtype`, 16-byte aligned, D * element size a multiple of 16
+ *   out       device [32 * 32] fp32: out[i * 32 + j] = <a_i, c_j>
+ */
+luvc_status luvc_selftest_screen_tile(const void* a, const void* c, int D, luvc_dtype dtype, float* out, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -23,7 +23,7 @@ EXPORTS = ("luvc_version", "luvc_last_error", "luvc_oim_plan", "luvc_oim_workspa
            "luvc_spu_cascade_keeps", "luvc_spu_stage",
            "luvc_oim_plan_anyres", "luvc_oim_ragged_workspace_bytes", "luvc_oim_merge_ragged",
            "luvc_spu_ragged_workspace_bytes", "luvc_spu_stage_ragged",
-           "luvc_profile_start", "luvc_profile_stop", "luvc_profile_kernel", "luvc_selftest_fdot2")
+           "luvc_profile_start", "luvc_profile_stop", "luvc_profile_kernel", "luvc_selftest_fdot2", "luvc_selftest_screen_tile")
 
 
 class LuvcPass(ctypes.Structure):
@@ -101,6 +101,8 @@ def lib() -> ctypes.CDLL:
     L.luvc_profile_kernel.restype = ctypes.c_char_p
     L.luvc_selftest_fdot2.argtypes = [vp, vp, i, i, vp, vp]
     L.luvc_selftest_fdot2.restype = i
+    L.luvc_selftest_screen_tile.argtypes = [vp, vp, i, i, vp, vp]
+    L.luvc_selftest_screen_tile.restype = i
     _lib = L
     return L
 
@@ -483,4 +485,14 @@ def luvc_selftest_fdot2(x, y, stream=None):
     assert x.is_contiguous() and y.is_contiguous()
     out = torch.empty((x.shape[0],), dtype=torch.float32, device=x.device)
     _check(lib().luvc_selftest_fdot2(_ptr(x), _ptr(y), x.shape[0], x.shape[1] // 2, _ptr(out), _stream(stream)))
+    return out
+
+
+def luvc_selftest_screen_tile(a, c, stream=None):
+    """a, c [32, D] (fp32 or bf16) -> [32, 32] fp32: the screening tile of the wide matching, <a_i, c_j> on the matrix cores."""
+    import torch
+    assert a.is_cuda and a.shape == c.shape and a.dim() == 2 and a.shape[0] == 32 and a.dtype == c.dtype
+    assert a.is_contiguous() and c.is_contiguous()
+    out = torch.empty((32, 32), dtype=torch.float32, device=a.device)
+    _check(lib().luvc_selftest_screen_tile(_ptr(a), _ptr(c), a.shape[1], _dtype_code(a), _ptr(out), _stream(stream)))
     return out

@@ -177,3 +177,58 @@ def test_wide_without_maps(oracle):
     torch.cuda.synchronize()
     np.testing.assert_array_equal(to_host_f64(out["x"]), ref["x"])
     np.testing.assert_array_equal(out["sizes"].cpu().numpy().astype(np.int64), ref["sizes"])
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("D", [8, 16, 24, 72, 520, 1280, 2048])
+def test_screening_tile_error_stays_inside_the_bound_the_decisions_assume(dtype, D):
+    """The 32 x 32 tile of dot products formed on the matrix cores in the storage precision against exact sums, on rows
+    chosen to provoke accumulation error: the screening of the wide matching assumes an error of at most D 2^-23 times
+    the sum of the magnitudes of the products (it budgets twice that, relative to the product of the norms)."""
+    rng = np.random.default_rng(D)
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    cases = {
+        "normal": (rng.standard_normal((32, D)), rng.standard_normal((32, D))),
+        "positive, equal magnitudes": (1.0 + rng.random((32, D)) / 128, 1.0 + rng.random((32, D)) / 128),
+        "wide range": (rng.standard_normal((32, D)) * 2.0 ** rng.integers(-20, 20, (32, D)), rng.standard_normal((32, D)) * 2.0 ** rng.integers(-20, 20, (32, D))),
+        "cancelling": (np.tile([1.0, -1.0], (32, D // 2)) * (1.0 + rng.random((32, D)) / 64), np.ones((32, D)) + rng.random((32, D)) / 64),
+        "one large term first": (np.concatenate([np.full((32, 1), 4096.0), rng.random((32, D - 1))], 1), np.concatenate([np.full((32, 1), 4096.0), rng.random((32, D - 1))], 1)),
+    }
+    for name, (a, c) in cases.items():
+        ta, tc = torch.from_numpy(a).to(tdt).cuda(), torch.from_numpy(c).to(tdt).cuda()
+        got = lv.luvc_selftest_screen_tile(ta, tc).cpu().numpy().astype(np.float64)
+        a64, c64 = ta.cpu().to(torch.float64).numpy(), tc.cpu().to(torch.float64).numpy()
+        exact = a64 @ c64.T
+        mags = np.abs(a64) @ np.abs(c64).T
+        worst = (np.abs(got - exact) / mags).max()
+        print(f"[screen tile] {dtype} D={D} {name}: worst error {worst:.3e} of the magnitudes, allowed {D * 2.0 ** -23:.3e}", flush=True)
+        assert worst <= D * 2.0 ** -23, (name, worst)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_wide_decisions_the_screening_cannot_tell(oracle, dtype):
+    """Lines of near-duplicate tokens (all cosines of a line within the screening's error of each other: every pair is
+    repeated in fp64), lines of identical tokens (exact ties: the lower position wins twice over), and a zero token."""
+    rng = np.random.default_rng(41)
+    base = rng.standard_normal((1, 1, 1, 64)).astype(np.float32)
+    for (H, W, passes, radius) in ((6, 24, [(W_AX, 2), (H_AX, 2)], 0), (3, 128, [(W_AX, 64)], 0), (4, 128, [(W_AX, 2)], 0),
+                                   (128, 2, [(H_AX, 5)], 3), (10, 12, [(W_AX, 6), (H_AX, 5)], 2)):
+        x = base + 1e-3 * rng.standard_normal((2, H, W, 64)).astype(np.float32)
+        x[0, 1] = x[0, 1, 0]                  # a row of identical tokens
+        x[1, :, 1] = x[1, 0, 1]               # a column of identical tokens
+        x[1, 2, W // 2] = 0.0
+        sizes = rng.integers(1, 4, (2, H, W))
+        run_wide(oracle, wl.cast_io(x, dtype), dtype, passes, radius, tag="close calls")
+        run_wide(oracle, wl.cast_io(x, dtype), dtype, passes, radius, sizes=sizes, tag="close calls+sizes")
+
+
+def test_wide_determinism():
+    rng = np.random.default_rng(43)
+    x = to_dev(wl.cast_io(wl.smooth_field(rng, 2, 40, 36, 136, 2.0) + 0.05 * rng.standard_normal((2, 40, 36, 136)).astype(np.float32), "bf16"), "bf16")
+    passes = [(W_AX, 2), (H_AX, 2)] * 2
+    a = lv.luvc_oim_merge_wide(x, passes, 0)
+    for _ in range(3):
+        b = lv.luvc_oim_merge_wide(x, passes, 0)
+        torch.cuda.synchronize()
+        for k in ("x", "sizes", "merged_map", "kept_map"):
+            assert torch.equal(a[k], b[k]), k
