@@ -442,6 +442,18 @@ def next_rows_leg(lv, torch, w, xs_oim, xs_spu, n_rot, tdt, code, es, stream, st
     ms, kern = _time_call(torch, lv, lambda i: lv.luvc_oim_merge_keyed(xs_oim[i % n_rot], keys[i % 2], passes, 1, workspace=ws, stream=stream, out=out), steps)
     res["oim_keyed"] = {"what": f"luvc_oim_merge_keyed, keys {B}x{H}x{W}x{Dm}, same schedule as the step", "ms_per_call": round(ms, 5), "kernels": kern}
 
+    # ---- the same keys with the paper's appendix setting: every destination of the line a candidate, merge number 2, three operations
+    wpasses = [(1, 2), (0, 2)] * 3
+    Hw, Ww = lv.out_grid(H, W, wpasses)
+    ws2 = torch.empty(lv.luvc_oim_keyed_workspace_bytes(B, H, W, D, Dm, code, wpasses, 0), dtype=torch.uint8, device=dev)
+    out2 = dict(x=torch.empty((B, Hw, Ww, D), dtype=tdt, device=dev), metric=torch.empty((B, Hw, Ww, Dm), dtype=tdt, device=dev),
+                sizes=torch.empty((B, Hw, Ww), dtype=torch.int32, device=dev), merged_map=torch.empty((B, H * W), dtype=torch.int32, device=dev),
+                kept_map=torch.empty((B, Hw * Ww), dtype=torch.int32, device=dev))
+    ms, kern = _time_call(torch, lv, lambda i: lv.luvc_oim_merge_keyed(xs_oim[i % n_rot], keys[i % 2], wpasses, 0, workspace=ws2, stream=stream, out=out2), steps)
+    res["oim_keyed_wide"] = {"what": f"luvc_oim_merge_keyed, keys {B}x{H}x{W}x{Dm}, whole-line matching, m = 2, passes (W,2),(H,2) x 3",
+                             "ms_per_call": round(ms, 5), "kernels": kern}
+    del ws2, out2
+
     # ---- V + log s on a tensor of the encoder grid's size
     sizes = torch.randint(1, 5, (B, H, W), dtype=torch.int32, device=dev)
     vout = torch.empty_like(xs_oim[0])

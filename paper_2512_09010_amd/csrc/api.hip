@@ -266,7 +266,7 @@ static luvc_status oim_merge_impl(const void* x, const int32_t* sizes_in, int B,
             int32_t* pm = merged_map ? ((pl.n == 1) ? merged_map : (int32_t*)(ws + L.maps[i])) : nullptr;
             lmaps[i] = pm;
             ln_in[i] = pl.h[i] * pl.w[i];
-            const luvc_status rc = oim_wide_lazy_pass(x, ws + L.lazy_ov, cur_i, cur_sz, cur_kp, B, H * W, pl.h[i], pl.w[i], D, dtype,
+            const luvc_status rc = oim_wide_lazy_pass(x, ws + L.lazy_ov, nullptr, nullptr, 0, cur_i, cur_sz, cur_kp, B, H * W, pl.h[i], pl.w[i], D, dtype,
                                                       passes[i].axis, passes[i].m, radius, L.lazy_cap, ov_base, oi, os, ok, pm, st);
             if (rc != LUVC_OK) return rc;
             ov_base += oim_wide_lazy_rows(pl.h[i], pl.w[i], passes[i].axis, passes[i].m);
@@ -361,7 +361,7 @@ luvc_status luvc_oim_merge_wide(const void* x, const int32_t* sizes_in, int B, i
 // runs its decisions and its two merges (features, metric) as separate stages on the general kernels
 struct KeyedLayout {
     OimLayout base;
-    size_t mbuf[2], bytes;          // ping-pong buffers of the merged metric between passes
+    size_t mbuf[2], mov, bytes;     // ping-pong buffers of the merged metric between passes; overlay of the metric (one launch per pass)
 };
 
 static KeyedLayout keyed_layout(int B, int D, int Dm, luvc_dtype dt, const OimPlan& pl, const luvc_oim_pass* passes, int radius)
@@ -378,6 +378,7 @@ static KeyedLayout keyed_layout(int B, int D, int Dm, luvc_dtype dt, const OimPl
         if (t > tok[0]) tok[0] = tok[1] = t;
     }
     for (int j = 0; j < 2; ++j) { K.mbuf[j] = off; off += align_up(tok[j] * Dm * esize(dt)); }
+    K.mov = off; off += align_up((size_t)B * (size_t)K.base.lazy_cap * Dm * esize(dt));
     K.bytes = off;
     return K;
 }
@@ -438,6 +439,41 @@ luvc_status luvc_oim_merge_keyed(const void* x, const void* metric, const int32_
     sc.absorb = (int32_t*)(ws + L.absorb);
     double* G = (double*)(ws + L.gram);
     int32_t* src_dest = (int32_t*)(ws + L.srcdest);
+
+    bool lazy = radius != 1 && vec_x && vec_m && (int64_t)H * W + L.lazy_cap < ((int64_t)1 << 31);
+    for (int i = 0; i < pl.n; ++i)
+        if ((passes[i].axis ? pl.w[i] : pl.h[i]) > kLazyMaxLen) lazy = false;
+    if (lazy) {
+        // wide matching on the metric, one launch per pass on grids of row ids; tokens and metric move once at the end
+        const int32_t *cur_i = nullptr, *cur_sz = sizes_in, *cur_kp = nullptr;
+        const int32_t* lmaps[kMaxPasses];
+        int32_t ln_in[kMaxPasses];
+        int ov_base = 0;
+        for (int i = 0; i < pl.n; ++i) {
+            const bool last = i + 1 == pl.n;
+            int32_t* oi = (int32_t*)(ws + L.lazy_idx[i & 1]);
+            int32_t* os = last ? sizes_out : (int32_t*)(ws + L.sbuf[i & 1]);
+            int32_t* ok = last ? kept_map : (int32_t*)(ws + L.kbuf[i & 1]);
+            int32_t* pm = merged_map ? ((pl.n == 1) ? merged_map : (int32_t*)(ws + L.maps[i])) : nullptr;
+            lmaps[i] = pm;
+            ln_in[i] = pl.h[i] * pl.w[i];
+            const luvc_status rc = oim_wide_lazy_pass(x, ws + L.lazy_ov, metric, ws + K.mov, Dm, cur_i, cur_sz, cur_kp, B, H * W, pl.h[i], pl.w[i],
+                                                      D, dtype, passes[i].axis, passes[i].m, radius, L.lazy_cap, ov_base, oi, os, ok, pm, st);
+            if (rc != LUVC_OK) return rc;
+            ov_base += oim_wide_lazy_rows(pl.h[i], pl.w[i], passes[i].axis, passes[i].m);
+            cur_i = oi;
+            cur_sz = os;
+            cur_kp = ok;
+        }
+        luvc_status rc = oim_wide_lazy_gather(x, ws + L.lazy_ov, cur_i, B, H * W, L.lazy_cap, Ho * Wo, D, dtype, x_out, st);
+        if (rc != LUVC_OK) return rc;
+        if (metric_out) {
+            rc = oim_wide_lazy_gather(metric, ws + K.mov, cur_i, B, H * W, L.lazy_cap, Ho * Wo, Dm, dtype, metric_out, st);
+            if (rc != LUVC_OK) return rc;
+        }
+        if (merged_map && pl.n > 1) return oim_compose(lmaps, ln_in, pl.n, B, H * W, merged_map, st);
+        return LUVC_OK;
+    }
 
     const void *cur_x = x, *cur_m = metric;
     const int32_t* cur_s = sizes_in;

@@ -39,7 +39,8 @@ luvc_status oim_wide_pass(const void* x, const int32_t* sizes_in, int B, int H, 
 // destinations).  Lines of at most kLazyMaxLen tokens, 16-byte aligned rows.
 constexpr int kLazyMaxLen = 128;
 int oim_wide_lazy_rows(int h, int w, int axis, int m);      // overlay rows per image that a pass may write
-luvc_status oim_wide_lazy_pass(const void* x, void* ov, const int32_t* idx_in, const int32_t* sizes_in, const int32_t* kept_in,
+// metric / ov_metric / Dm: the tensor the decisions are taken on and its overlay (merged like x), or NULL / NULL / 0: x itself
+luvc_status oim_wide_lazy_pass(const void* x, void* ov, const void* metric, void* ov_metric, int Dm, const int32_t* idx_in, const int32_t* sizes_in, const int32_t* kept_in,
                                int B, int n0, int h, int w, int D, luvc_dtype dt, int axis, int m, int radius, int cap, int ov_base,
                                int32_t* idx_out, int32_t* sizes_out, int32_t* kept_out, int32_t* pass_map, hipStream_t st);
 luvc_status oim_wide_lazy_gather(const void* x, const void* ov, const int32_t* idx, int B, int n0, int cap, int n_out_per, int D,

@@ -48,9 +48,9 @@ struct LazyGeom {
 __host__ __device__ inline int lazy_row_stride(int n_dst) { return n_dst <= 4 ? 4 : 32 * ((n_dst - 4 + 31) / 32) + 4; }
 
 template <typename T>
-__device__ __forceinline__ const T* row_of(const T* x, const T* ov, int64_t b, int id, const LazyGeom& g)
+__device__ __forceinline__ const T* row_of(const T* x, const T* ov, int64_t b, int id, const LazyGeom& g, int D)
 {
-    return id < g.n0 ? x + (b * g.n0 + id) * g.D : ov + (b * g.cap + (id - g.n0)) * g.D;
+    return id < g.n0 ? x + (b * g.n0 + id) * D : ov + (b * g.cap + (id - g.n0)) * D;
 }
 
 }  // namespace
@@ -199,7 +199,8 @@ selftest_screen_tile(const T* __restrict__ a, const T* __restrict__ c, int D, fl
 constexpr int kLazyLoads = 8;                    // steps of the screening contraction fetched before the first is used
 template <typename T>
 __global__ void __launch_bounds__(256)
-oim_wide_line(const T* __restrict__ x, T* ov, const int32_t* __restrict__ idx_in /* null: identity */,
+oim_wide_line(const T* __restrict__ x, T* ov, const T* __restrict__ xk /* metric [.., Dk] the decisions are taken on, or null: x */,
+              T* ovk /* its overlay */, int Dk, const int32_t* __restrict__ idx_in /* null: identity */,
               const int32_t* __restrict__ sizes_in /* null: ones */, const int32_t* __restrict__ kept_in /* null: identity */,
               LazyGeom g, int32_t* __restrict__ idx_out, int32_t* __restrict__ sizes_out, int32_t* __restrict__ kept_out /* or null */,
               int32_t* __restrict__ pass_map /* or null */)
@@ -242,7 +243,11 @@ oim_wide_line(const T* __restrict__ x, T* ov, const int32_t* __restrict__ idx_in
     auto in_flat = [&](int p) -> int { return g.axis ? line * g.w + p : p * g.w + line; };
     auto out_flat = [&](int q) -> int { return g.axis ? line * Wo + q : q * Wo + line; };
     // eps: bound of |screened cosine - fp64 cosine| (head of this file); both selections use 2 eps
-    const float tau = 2.f * (float)(g.D + 2) * 2.3841858e-7f;
+    // the tensor the decisions are taken on
+    const T* dx = xk ? xk : x;
+    const T* dov = xk ? ovk : ov;
+    const int dD = xk ? Dk : g.D;
+    const float tau = 2.f * (float)(dD + 2) * 2.3841858e-7f;
 
     for (int p = tid; p < len; p += blockDim.x) {
         const int f = in_flat(p);
@@ -265,20 +270,20 @@ oim_wide_line(const T* __restrict__ x, T* ov, const int32_t* __restrict__ idx_in
             const int ts = t / tiles_d, td = t % tiles_d;
             const int js = ts * 32 + r, jd = td * 32 + r;
             const bool has_s = js < n_src, has_d = jd < n_dst;
-            const T* tok_s = row_of<T>(x, ov, b, has_s ? rid[2 * js] : rid[0], g);
-            const T* tok_d = row_of<T>(x, ov, b, has_d ? rid[2 * jd + 1] : rid[0], g);
+            const T* tok_s = row_of<T>(dx, dov, b, has_s ? rid[2 * js] : rid[0], g, dD);
+            const T* tok_d = row_of<T>(dx, dov, b, has_d ? rid[2 * jd + 1] : rid[0], g, dD);
             f32x16 acc;
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[v] = 0.f;
             double na = 0.0, nc = 0.0;
             // wavefront w takes steps w, w + 4, ... of KS channels, a lane its half of each; the trip count is the same in
             // every lane (the matrix instructions want the whole wavefront), pieces past the end of the token are zeros
-            for (int d0 = wave * sc::KS; d0 < g.D; d0 += 4 * sc::KS * kLazyLoads) {
+            for (int d0 = wave * sc::KS; d0 < dD; d0 += 4 * sc::KS * kLazyLoads) {
                 u32x4 ra[kLazyLoads], rc[kLazyLoads];
 #pragma unroll
                 for (int u = 0; u < kLazyLoads; ++u) {
-                    ra[u] = piece(tok_s, g.D, d0 + 4 * sc::KS * u + kh * sc::KL, has_s);
-                    rc[u] = piece(tok_d, g.D, d0 + 4 * sc::KS * u + kh * sc::KL, has_d);
+                    ra[u] = piece(tok_s, dD, d0 + 4 * sc::KS * u + kh * sc::KL, has_s);
+                    rc[u] = piece(tok_d, dD, d0 + 4 * sc::KS * u + kh * sc::KL, has_d);
                 }
 #pragma unroll
                 for (int u = 0; u < kLazyLoads; ++u) {
@@ -375,8 +380,8 @@ oim_wide_line(const T* __restrict__ x, T* ov, const int32_t* __restrict__ idx_in
             const int pr1 = pairs[i], pr2 = pairs[two ? i + 4 : i];
             const int a1 = 2 * (pr1 >> 8), c1 = 2 * (pr1 & 255) + 1, a2 = 2 * (pr2 >> 8), c2 = 2 * (pr2 & 255) + 1;
             double d1, d2;
-            dot64_wave2<T>(row_of<T>(x, ov, b, rid[a1], g), row_of<T>(x, ov, b, rid[c1], g), row_of<T>(x, ov, b, rid[a2], g),
-                           row_of<T>(x, ov, b, rid[c2], g), g.D, lane, d1, d2);
+            dot64_wave2<T>(row_of<T>(dx, dov, b, rid[a1], g, dD), row_of<T>(dx, dov, b, rid[c1], g, dD), row_of<T>(dx, dov, b, rid[a2], g, dD),
+                           row_of<T>(dx, dov, b, rid[c2], g, dD), dD, lane, d1, d2);
             if (lane == 0) {
                 E[i] = d1 / (nrm[a1] * nrm[c1]);
                 if (two) E[i + 4] = d2 / (nrm[a2] * nrm[c2]);
@@ -453,19 +458,25 @@ oim_wide_line(const T* __restrict__ x, T* ov, const int32_t* __restrict__ idx_in
 
     // ------------------------------------------------------------------ 4. the merged destinations
     // the destination's pieces and those of the first two sources are in flight together
+    // (features, and the metric too when the decisions were taken on one: it follows its own decisions)
     const int n_abs = tot[1] + tot[2];
-    for (int k = wave; k < n_abs; k += 4) {
+    for (int kk = wave; kk < (xk ? 2 : 1) * n_abs; kk += 4) {
+        const bool on_metric = kk >= n_abs;
+        const int k = on_metric ? kk - n_abs : kk;
+        const T* mx = on_metric ? xk : x;
+        T* mov = on_metric ? ovk : ov;
+        const int mD = on_metric ? Dk : g.D;
         const int c = dlist[k];
-        const T* xp = row_of<T>(x, ov, b, rid[c], g);
-        T* o = ov + (b * g.cap + g.ov_base + line * g.per_line + k) * g.D;
+        const T* xp = row_of<T>(mx, mov, b, rid[c], g, mD);
+        T* o = mov + (b * g.cap + g.ov_base + line * g.per_line + k) * mD;
         const double sp = (double)sz[c], dS = (double)snew[c];
         const unsigned long long hits = __ballot(lane < n_src && merged[2 * lane] && best[lane] == c);   // n_src <= 64
-        for (int d0 = 0; d0 < g.D; d0 += 64 * V * 4) {
+        for (int d0 = 0; d0 < mD; d0 += 64 * V * 4) {
             double acc[4][V];
             {
                 u32x4 rp[4];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) rp[u] = piece(xp, g.D, d0 + (u * 64 + lane) * V, true);
+                for (int u = 0; u < 4; ++u) rp[u] = piece(xp, mD, d0 + (u * 64 + lane) * V, true);
                 unsigned long long h = hits;
                 bool first = true;
                 do {
@@ -473,13 +484,13 @@ oim_wide_line(const T* __restrict__ x, T* ov, const int32_t* __restrict__ idx_in
                     h &= h - 1;
                     const int j2 = h ? (int)__builtin_ctzll(h) : -1;
                     h &= h - 1;
-                    const T* x1 = row_of<T>(x, ov, b, rid[j1 >= 0 ? 2 * j1 : 0], g);
-                    const T* x2 = row_of<T>(x, ov, b, rid[j2 >= 0 ? 2 * j2 : 0], g);
+                    const T* x1 = row_of<T>(mx, mov, b, rid[j1 >= 0 ? 2 * j1 : 0], g, mD);
+                    const T* x2 = row_of<T>(mx, mov, b, rid[j2 >= 0 ? 2 * j2 : 0], g, mD);
                     u32x4 r1[4], r2[4];
 #pragma unroll
                     for (int u = 0; u < 4; ++u) {
-                        r1[u] = piece(x1, g.D, d0 + (u * 64 + lane) * V, j1 >= 0);
-                        r2[u] = piece(x2, g.D, d0 + (u * 64 + lane) * V, j2 >= 0);
+                        r1[u] = piece(x1, mD, d0 + (u * 64 + lane) * V, j1 >= 0);
+                        r2[u] = piece(x2, mD, d0 + (u * 64 + lane) * V, j2 >= 0);
                     }
                     const double s1 = j1 >= 0 ? (double)sz[2 * j1] : 0.0, s2 = j2 >= 0 ? (double)sz[2 * j2] : 0.0;
 #pragma unroll
@@ -507,7 +518,7 @@ oim_wide_line(const T* __restrict__ x, T* ov, const int32_t* __restrict__ idx_in
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const int d = d0 + (u * 64 + lane) * V;
-                if (d >= g.D) continue;
+                if (d >= mD) continue;
                 T r[V];
 #pragma unroll
                 for (int i = 0; i < V; ++i) tr::store(&r[i], acc[u][i] / dS);
@@ -551,7 +562,7 @@ int oim_wide_lazy_rows(int h, int w, int axis, int m)
 }
 
 template <typename T>
-static luvc_status run_lazy_pass(const T* x, T* ov, const int32_t* idx_in, const int32_t* sizes_in, const int32_t* kept_in,
+static luvc_status run_lazy_pass(const T* x, T* ov, const T* xk, T* ovk, int Dk, const int32_t* idx_in, const int32_t* sizes_in, const int32_t* kept_in,
                                  int B, int n0, int h, int w, int D, int axis, int m, int radius, int cap, int ov_base,
                                  int32_t* idx_out, int32_t* sizes_out, int32_t* kept_out, int32_t* pass_map, hipStream_t st)
 {
@@ -563,19 +574,19 @@ static luvc_status run_lazy_pass(const T* x, T* ov, const int32_t* idx_in, const
     const int sd = lazy_row_stride(n_dst);
     const size_t lds = sizeof(double) * ((size_t)5 * len) + sizeof(float) * ((size_t)n_src * (2 * n_dst > sd ? 2 * n_dst : sd) + 4096 + n_src + len) +
                        sizeof(int) * ((size_t)6 * len + 3 * n_src + 6) + (size_t)2 * len + 16;
-    LUVC_LAUNCH("oim_wide_line", (oim_wide_line<T>), dim3((unsigned)(B * nlines)), dim3(256), lds, st, x, ov, idx_in, sizes_in, kept_in, g,
+    LUVC_LAUNCH("oim_wide_line", (oim_wide_line<T>), dim3((unsigned)(B * nlines)), dim3(256), lds, st, x, ov, xk, ovk, Dk, idx_in, sizes_in, kept_in, g,
                 idx_out, sizes_out, kept_out, pass_map);
     return check_launch("oim pass (wide matching, one launch)");
 }
 
-luvc_status oim_wide_lazy_pass(const void* x, void* ov, const int32_t* idx_in, const int32_t* sizes_in, const int32_t* kept_in,
+luvc_status oim_wide_lazy_pass(const void* x, void* ov, const void* metric, void* ov_metric, int Dm, const int32_t* idx_in, const int32_t* sizes_in, const int32_t* kept_in,
                                int B, int n0, int h, int w, int D, luvc_dtype dt, int axis, int m, int radius, int cap, int ov_base,
                                int32_t* idx_out, int32_t* sizes_out, int32_t* kept_out, int32_t* pass_map, hipStream_t st)
 {
     if (dt == LUVC_F32)
-        return run_lazy_pass<float>((const float*)x, (float*)ov, idx_in, sizes_in, kept_in, B, n0, h, w, D, axis, m, radius, cap, ov_base,
+        return run_lazy_pass<float>((const float*)x, (float*)ov, (const float*)metric, (float*)ov_metric, Dm, idx_in, sizes_in, kept_in, B, n0, h, w, D, axis, m, radius, cap, ov_base,
                                     idx_out, sizes_out, kept_out, pass_map, st);
-    return run_lazy_pass<bf16_t>((const bf16_t*)x, (bf16_t*)ov, idx_in, sizes_in, kept_in, B, n0, h, w, D, axis, m, radius, cap, ov_base,
+    return run_lazy_pass<bf16_t>((const bf16_t*)x, (bf16_t*)ov, (const bf16_t*)metric, (bf16_t*)ov_metric, Dm, idx_in, sizes_in, kept_in, B, n0, h, w, D, axis, m, radius, cap, ov_base,
                                  idx_out, sizes_out, kept_out, pass_map, st);
 }
 

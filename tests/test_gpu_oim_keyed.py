@@ -158,6 +158,43 @@ def test_keyed_pair_without_metric_and_maps(oracle):
     np.testing.assert_array_equal(out["sizes"].cpu().numpy().astype(np.int64), ref["sizes"])
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("B,H,W,D,Dm,passes,radius", [
+    (2, 24, 20, 136, 64, [(W_AX, 2), (H_AX, 2)] * 3, 0),        # the appendix setting on the keys: whole line, merge number 2, three operations
+    (1, 40, 36, 72, 128, [(H_AX, 5), (W_AX, 18), (H_AX, 1)], 2),
+    (1, 3, 128, 32, 16, [(W_AX, 64)], 0),                        # longest line of the one-launch passes, every source merged
+    (1, 2, 140, 32, 16, [(W_AX, 3)], 0),                         # beyond it: three launches per pass and tensor
+])
+def test_keyed_wide_matching(oracle, dtype, B, H, W, D, Dm, passes, radius):
+    rng = np.random.default_rng(B * 1000 + H * 100 + W * 10 + D + Dm + radius)
+    x = wl.cast_io(rng.standard_normal((B, H, W, D)).astype(np.float32), dtype)
+    keys = wl.cast_io(wl.smooth_field(rng, B, H, W, Dm, 2.0) + 0.2 * rng.standard_normal((B, H, W, Dm)).astype(np.float32), dtype)
+    run_keyed(oracle, x, keys, dtype, passes, radius, tag="wide keys")
+    sizes = rng.integers(1, 5, (B, H, W))
+    run_keyed(oracle, x, keys, dtype, passes, radius, sizes=sizes, tag="wide keys+sizes")
+
+
+def test_keyed_wide_one_launch_passes_and_three_launch_passes_agree():
+    """The same keyed call on 16-byte aligned keys (row ids between the passes, one launch per pass) and on a copy of the
+    keys that starts 8 bytes off (every pass materialised, four launches per pass): identical outputs."""
+    rng = np.random.default_rng(47)
+    B, H, W, D, Dm = 2, 20, 24, 72, 40
+    x = torch.from_numpy(rng.standard_normal((B, H, W, D)).astype(np.float32)).to(torch.bfloat16).cuda()
+    k = torch.from_numpy(wl.smooth_field(rng, B, H, W, Dm, 2.0) + 0.2 * rng.standard_normal((B, H, W, Dm)).astype(np.float32)).to(torch.bfloat16).cuda()
+    flat = torch.empty(k.numel() + 4, dtype=torch.bfloat16, device="cuda")
+    flat[4:] = k.reshape(-1)
+    k_off = flat[4:].view(B, H, W, Dm)
+    assert k.data_ptr() % 16 == 0 and k_off.data_ptr() % 16 == 8
+    passes = [(W_AX, 2), (H_AX, 2)] * 2
+    a = lv.luvc_oim_merge_keyed(x, k, passes, 0)
+    b = lv.luvc_oim_merge_keyed(x, k_off, passes, 0)
+    c = lv.luvc_oim_merge_keyed(x, k, passes, 0, want_metric=False, want_maps=False)
+    torch.cuda.synchronize()
+    for key in ("x", "metric", "sizes", "merged_map", "kept_map"):
+        assert torch.equal(a[key], b[key]), key
+    assert torch.equal(a["x"], c["x"]) and torch.equal(a["sizes"], c["sizes"]) and c["metric"] is None
+
+
 @pytest.mark.parametrize("dtype,shape", [("f32", (3, 7, 33)), ("bf16", (2, 64, 1280)), ("bf16", (5, 3, 10)), ("f32", (1, 19, 256))])
 def test_value_enhance(oracle, dtype, shape):
     rng = np.random.default_rng(sum(shape))
