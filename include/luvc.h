@@ -116,8 +116,12 @@ luvc_status luvc_oim_merge(const void* x, const int32_t* sizes_in,
  * destination b of the line with |b - a| <= 2 * radius - 1, or every destination of the line when
  * radius = 0; a destination can then absorb several sources (size-weighted mean over all of them,
  * added in ascending position).  radius = 1 is luvc_oim_merge itself.
- * The source x destination dot products of every line are evaluated in fp64 on the matrix cores.
- * Limits: lines of at most 2048 tokens when radius != 1.
+ * The decisions are fp64 decisions.  Lines of at most 128 tokens with 16-byte aligned rows (x, x_out and D * element
+ * size multiples of 16) are screened on the matrix cores in the storage precision and only the pairs the screening cannot
+ * tell are repeated in fp64; between the passes of such a call the grids are kept as row indices and the tokens are
+ * moved once, at the end.  Longer lines or unaligned rows: every dot product in fp64 on the matrix cores, every pass
+ * written out.  The results are the same either way.
+ * Limits: lines of at most 2048 tokens and images of less than 2 GiB when radius != 1.
  * Workspace: luvc_oim_wide_workspace_bytes for the same arguments.
  */
 size_t luvc_oim_wide_workspace_bytes(int B, int H, int W, int D, luvc_dtype dtype,
@@ -136,7 +140,10 @@ luvc_status luvc_oim_merge_wide(const void* x, const int32_t* sizes_in,
  *   metric      device [B,H,W,Dm] dtype
  *   metric_out  device [B,H',W',Dm] dtype, or NULL
  *   radius      1 = adjacent destinations, R > 1 = within 2R-1 positions, 0 = the whole line
- * Runs on the general kernels (separate decision and merge launches).
+ * A pair of halving passes on different axes with adjacent matching (radius 1), keys of at most 1 KB per token and
+ * 16-byte aligned rows of x, metric and the outputs runs as one launch; wide matching (radius != 1) on lines of at most
+ * 128 tokens with aligned rows runs one launch per pass like luvc_oim_merge_wide; anything else runs decisions and
+ * merges (tokens, metric) as separate launches.  The results are the same either way.
  */
 size_t luvc_oim_keyed_workspace_bytes(int B, int H, int W, int D, int Dm, luvc_dtype dtype,
                                       const luvc_oim_pass* passes, int n_passes, int radius);
