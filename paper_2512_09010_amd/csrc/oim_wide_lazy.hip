@@ -530,6 +530,16 @@ oim_wide_line(const T* __restrict__ x, T* ov, const T* __restrict__ xk /* metric
 
 // ------------------------------------------------------------------ the rows behind the final ids
 typedef unsigned int lazy_u32x4 __attribute__((__vector_size__(16)));
+__device__ __forceinline__ const unsigned char* lazy_row(const unsigned char* x, const unsigned char* ov, const int32_t* idx, int64_t row,
+                                                         int n0, int cap, int n_out_per, int row_bytes)
+{
+    const int64_t b = row / n_out_per;
+    int id = idx[row];
+    id = id < 0 ? 0 : (id >= n0 + cap ? n0 + cap - 1 : id);            // ids come from oim_wide_line; stay in bounds regardless
+    return id < n0 ? x + (b * n0 + id) * (int64_t)row_bytes : ov + (b * cap + (id - n0)) * (int64_t)row_bytes;
+}
+
+// one wavefront per row
 __global__ void __launch_bounds__(256)
 oim_wide_gather(const unsigned char* __restrict__ x, const unsigned char* __restrict__ ov, const int32_t* __restrict__ idx,
                 int n0, int cap, int n_out_per, int row_bytes, int64_t n_rows, unsigned char* __restrict__ x_out)
@@ -537,10 +547,7 @@ oim_wide_gather(const unsigned char* __restrict__ x, const unsigned char* __rest
     const int64_t row = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     const int lane = threadIdx.x & 63;
     if (row >= n_rows) return;
-    const int64_t b = row / n_out_per;
-    int id = idx[row];
-    id = id < 0 ? 0 : (id >= n0 + cap ? n0 + cap - 1 : id);            // ids come from oim_wide_line; stay in bounds regardless
-    const unsigned char* in = id < n0 ? x + (b * n0 + id) * (int64_t)row_bytes : ov + (b * cap + (id - n0)) * (int64_t)row_bytes;
+    const unsigned char* in = lazy_row(x, ov, idx, row, n0, cap, n_out_per, row_bytes);
     unsigned char* o = x_out + row * (int64_t)row_bytes;
     // eight 16-byte pieces per lane in flight before the first store; the descriptors bound every piece
     const __amdgpu_buffer_rsrc_t ri = __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned char*>(in), 0, row_bytes, 0x00020000);
@@ -552,6 +559,23 @@ oim_wide_gather(const unsigned char* __restrict__ x, const unsigned char* __rest
 #pragma unroll
         for (int k = 0; k < 8; ++k) __builtin_amdgcn_raw_buffer_store_b128(v[k], ro, base + k * 1024 + lane * 16, 0, 2);
     }
+}
+
+// short rows (at most 512 bytes, e.g. the keys of one attention head): LPR = 16 or 32 lanes per row, several rows per
+// wavefront, so that a launch has a quarter or half of the wavefronts - each is three memory round trips long whatever it moves
+template <int LPR>
+__global__ void __launch_bounds__(256)
+oim_wide_gather_short(const unsigned char* __restrict__ x, const unsigned char* __restrict__ ov, const int32_t* __restrict__ idx,
+                      int n0, int cap, int n_out_per, int row_bytes, int64_t n_rows, unsigned char* __restrict__ x_out)
+{
+    constexpr int RPW = 64 / LPR;
+    const int lane = threadIdx.x & 63, sub = lane % LPR;
+    const int64_t row = (((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6) * RPW + lane / LPR;
+    if (row >= n_rows) return;
+    const unsigned char* in = lazy_row(x, ov, idx, row, n0, cap, n_out_per, row_bytes);
+    unsigned char* o = x_out + row * (int64_t)row_bytes;
+    const int off = sub * 16;
+    if (off < row_bytes) *reinterpret_cast<lazy_u32x4*>(o + off) = *reinterpret_cast<const lazy_u32x4*>(in + off);
 }
 
 // ------------------------------------------------------------------ host side
@@ -595,6 +619,15 @@ luvc_status oim_wide_lazy_gather(const void* x, const void* ov, const int32_t* i
 {
     const int64_t rows = (int64_t)B * n_out_per;
     const int row_bytes = D * (dt == LUVC_F32 ? 4 : 2);
+    if (row_bytes <= 512) {
+        const int rpw = row_bytes <= 256 ? 4 : 2;
+        const unsigned grid = (unsigned)(((rows + rpw - 1) / rpw * 64 + 255) / 256);
+        if (rpw == 4) LUVC_LAUNCH("oim_wide_gather", (oim_wide_gather_short<16>), dim3(grid), dim3(256), 0, st, (const unsigned char*)x, (const unsigned char*)ov, idx,
+                                  n0, cap, n_out_per, row_bytes, rows, (unsigned char*)x_out);
+        else          LUVC_LAUNCH("oim_wide_gather", (oim_wide_gather_short<32>), dim3(grid), dim3(256), 0, st, (const unsigned char*)x, (const unsigned char*)ov, idx,
+                                  n0, cap, n_out_per, row_bytes, rows, (unsigned char*)x_out);
+        return check_launch("oim wide matching, output rows");
+    }
     const unsigned grid = (unsigned)((rows * 64 + 255) / 256);
     LUVC_LAUNCH("oim_wide_gather", oim_wide_gather, dim3(grid), dim3(256), 0, st, (const unsigned char*)x, (const unsigned char*)ov, idx,
                 n0, cap, n_out_per, row_bytes, rows, (unsigned char*)x_out);
