@@ -223,3 +223,25 @@ def test_chained_step_on_the_gpus_own_bits(oracle, i):
     assert rel.max() <= 1e-5
     np.testing.assert_array_equal(pr["kept_idx"].cpu().numpy(), pr_ref["kept_idx"])
     np.testing.assert_array_equal(to_host_f64(pr["x"]), pr_ref["x"])
+
+
+@pytest.mark.parametrize("i", [1, 2, 3])
+def test_keyed_calls_at_full_size(oracle, i):
+    """The calls that decide on keys, on the full encoder grids of the batch workloads (all grids of the batch, keys of
+    one attention head cut from the tokens): the hot path's schedule on the fused pair kernel, and the appendix setting
+    (whole line, merge number 2, two operations) on the one-launch passes, element by element against the oracle."""
+    from gpu_util import oim_reference
+    w = wl.workload(i)
+    x = wl.oim_input(w)
+    Dm = 128
+    keys = np.ascontiguousarray(x[..., 256:256 + Dm])
+    for passes, radius in ((w.oim_calls[0], 1), ([(1, 2), (0, 2)] * 2, 0)):
+        print(f"[full keyed] {w.name} x={x.shape} keys={keys.shape} passes={passes} radius={radius}", flush=True)
+        out = lv.luvc_oim_merge_keyed(to_dev(x, w.dtype), to_dev(keys, w.dtype), passes, radius)
+        torch.cuda.synchronize()
+        ref = oim_reference(oracle, wl.widen(x, w.dtype), passes, out["merged_map"].cpu().numpy(), w.dtype, R=radius, metric=wl.widen(keys, w.dtype))
+        np.testing.assert_array_equal(out["sizes"].cpu().numpy().astype(np.int64), ref["sizes"])
+        np.testing.assert_array_equal(out["merged_map"].cpu().numpy(), ref["merged_map"])
+        np.testing.assert_array_equal(out["kept_map"].cpu().numpy(), ref["kept_map"])
+        np.testing.assert_array_equal(to_host_f64(out["x"]), ref["x"])
+        np.testing.assert_array_equal(to_host_f64(out["metric"]), ref["metric"])
