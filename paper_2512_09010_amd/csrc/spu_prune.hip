@@ -32,6 +32,20 @@ __device__ __forceinline__ uint32_t wave_scan_incl(uint32_t v)
     return v;
 }
 
+// largest value of the wavefront in every lane's hands: DPP row steps, then the four row results through readlane
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
+{
+    auto mx = [](uint32_t a, int b) { return a > (uint32_t)b ? a : (uint32_t)b; };
+    v = mx(v, __builtin_amdgcn_update_dpp((int)v, (int)v, 0xB1, 0xf, 0xf, false));     // quad_perm [1,0,3,2]
+    v = mx(v, __builtin_amdgcn_update_dpp((int)v, (int)v, 0x4E, 0xf, 0xf, false));     // quad_perm [2,3,0,1]
+    v = mx(v, __builtin_amdgcn_update_dpp((int)v, (int)v, 0x141, 0xf, 0xf, false));    // row_half_mirror
+    v = mx(v, __builtin_amdgcn_update_dpp((int)v, (int)v, 0x140, 0xf, 0xf, false));    // row_mirror
+    const uint32_t r0 = (uint32_t)__builtin_amdgcn_readlane((int)v, 0), r1 = (uint32_t)__builtin_amdgcn_readlane((int)v, 16),
+                   r2 = (uint32_t)__builtin_amdgcn_readlane((int)v, 32), r3 = (uint32_t)__builtin_amdgcn_readlane((int)v, 48);
+    const uint32_t a = r0 > r1 ? r0 : r1, c = r2 > r3 ? r2 : r3;
+    return a > c ? a : c;
+}
+
 constexpr int kSelThreads = 1024;
 
 // inclusive block scan of one int per thread; returns the inclusive prefix, *total gets the block sum
@@ -180,9 +194,7 @@ spu_prune_fused(const unsigned char* __restrict__ x, const float* __restrict__ s
 {
     __shared__ int32_t kept[kFusedMaxN];
     __shared__ int hist[4][256];                       // one histogram per digit pass: none has to be cleared in between
-    __shared__ uint32_t wave_tot[4];
-    __shared__ uint32_t sh_prefix;
-    __shared__ int sh_remaining;
+    __shared__ uint32_t wave_tot[4], wave_hi[4], wave_lo[4];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int g = blockIdx.x, G = gridDim.x, b = blockIdx.y;
     const float* s = scores + (int64_t)b * N;
@@ -193,36 +205,55 @@ spu_prune_fused(const unsigned char* __restrict__ x, const float* __restrict__ s
 #pragma unroll
     for (int i = 0; i < kFusedKeys; ++i) key[i] = (i < K && n0 + i < N) ? score_key(s[n0 + i]) : 0u;
     hist[0][tid] = 0; hist[1][tid] = 0; hist[2][tid] = 0; hist[3][tid] = 0;
+    // Largest and smallest key of the sample: the bits above the highest one in which they differ are common to all
+    // keys and need no digit pass (scores of one sample share sign and most of the exponent, so the first of four
+    // 8-bit passes would pile every key onto one or two counters - same-address LDS atomics, one after the other).
+    uint32_t hi = 0u, lo = 0xffffffffu;
+#pragma unroll
+    for (int i = 0; i < kFusedKeys; ++i)
+        if (i < K && n0 + i < N) { hi = key[i] > hi ? key[i] : hi; lo = key[i] < lo ? key[i] : lo; }
+    hi = wave_max_u32(hi);
+    lo = ~wave_max_u32(~lo);
+    if (lane == 0) { wave_hi[wave] = hi; wave_lo[wave] = lo; }
     __syncthreads();
+#pragma unroll
+    for (int w = 0; w < 4; ++w) { hi = wave_hi[w] > hi ? wave_hi[w] : hi; lo = wave_lo[w] < lo ? wave_lo[w] : lo; }
+    const int nb = 32 - __clz((int)(hi ^ lo));         // the keys differ in their low nb bits only (0: all equal)
 
-    uint32_t prefix = 0, mask = 0;
+    // MSD radix select on those bits, 8 at a time (the last pass takes what is left).  Every wavefront scans the
+    // histogram of a pass on its own - same counters, same result - so a pass costs one barrier and nothing is
+    // handed from wavefront to wavefront.
+    uint32_t prefix = nb >= 32 ? 0u : (hi >> nb) << nb, mask = nb >= 32 ? 0u : ~((1u << nb) - 1u);
     int remaining = n_keep;                            // still to pick among keys matching the prefix
-    for (int shift = 24, pass = 0; shift >= 0; shift -= 8, ++pass) {
+    for (int top = nb, pass = 0; top > 0; top -= 8, ++pass) {
+        const int shift = top > 8 ? top - 8 : 0, width = top - shift;
+        const uint32_t dmask = (1u << width) - 1u;
         int* h_pass = hist[pass];
 #pragma unroll
         for (int i = 0; i < kFusedKeys; ++i)
-            if (i < K && n0 + i < N && (key[i] & mask) == prefix) atomicAdd(&h_pass[(key[i] >> shift) & 255u], 1);
+            if (i < K && n0 + i < N && (key[i] & mask) == prefix) atomicAdd(&h_pass[(key[i] >> shift) & dmask], 1);
         __syncthreads();
-        if (wave == 0) {
-            // lane l looks at digits 255 - 4 l .. 252 - 4 l, largest first
-            int h[4], sum = 0;
+        // lane l looks at digits 255 - 4 l .. 252 - 4 l, largest first
+        int h[4], sum = 0;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) { h[j] = h_pass[255 - 4 * lane - j]; sum += h[j]; }
-            const int incl = (int)wave_scan_incl((uint32_t)sum);
-            int above = incl - sum;                    // tokens with a larger digit
+        for (int j = 0; j < 4; ++j) { h[j] = h_pass[255 - 4 * lane - j]; sum += h[j]; }
+        const int incl = (int)wave_scan_incl((uint32_t)sum);
+        int above = incl - sum;                        // tokens with a larger digit
+        int digit = 0, left = 0;
+        bool found = false;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                if (above < remaining && remaining <= above + h[j]) {
-                    sh_prefix = prefix | ((uint32_t)(255 - 4 * lane - j) << shift);
-                    sh_remaining = remaining - above;
-                }
-                above += h[j];
-            }
+        for (int j = 0; j < 4; ++j) {
+            if (above < remaining && remaining <= above + h[j]) { digit = 255 - 4 * lane - j; left = remaining - above; found = true; }
+            above += h[j];
         }
-        __syncthreads();
-        prefix = sh_prefix;
-        remaining = sh_remaining;
-        mask |= 255u << shift;
+        const unsigned long long who = __ballot(found);
+        if (who) {                                     // one lane at most (none only when nothing is kept)
+            const int src = (int)__builtin_ctzll(who);
+            digit = __builtin_amdgcn_readlane(digit, src);
+            remaining = __builtin_amdgcn_readlane(left, src);
+        }
+        prefix |= (uint32_t)digit << shift;
+        mask |= dmask << shift;
     }
     const uint32_t T = prefix;                         // key of the n_keep-th largest score
     const int take_eq = remaining;                     // tokens with key == T that are kept (lowest indices)
