@@ -156,6 +156,39 @@ def test_wide_matching_arguments(L):
     assert rc == lv.LUVC_ERR_UNSUPPORTED                                                  # line longer than the wide path takes
 
 
+def test_wide_and_keyed_workspaces_cover_the_one_launch_passes(L):
+    """The workspace of a wide-matching call holds what the one-launch passes need on top of the three-launch ones: two
+    grids of row ids and a row per merged destination (at most m per line and pass); the keyed call adds the same rows
+    for the keys.  Sizes grow with the schedule and shrink to the plain call's for radius 1."""
+    B, H, W, D, Dm = 2, 24, 20, 64, 16
+    one = [(1, 2)]
+    three = [(1, 2), (0, 2), (1, 2)]
+    w1 = lv.luvc_oim_wide_workspace_bytes(B, H, W, D, lv.LUVC_BF16, one, 0)
+    w3 = lv.luvc_oim_wide_workspace_bytes(B, H, W, D, lv.LUVC_BF16, three, 0)
+    ids = 2 * B * H * W * 4
+    rows1 = B * H * 2 * D * 2                                   # one pass along W: 2 merged destinations per row of the grid
+    rows3 = rows1 + B * (W - 2) * 2 * D * 2 + B * (H - 2) * 2 * D * 2
+    assert w1 >= ids + rows1 and w3 >= ids + rows3 and w3 > w1
+    k3 = lv.luvc_oim_keyed_workspace_bytes(B, H, W, D, Dm, lv.LUVC_BF16, three, 0)
+    assert k3 >= w3 + rows3 // D * Dm
+    k1 = lv.luvc_oim_keyed_workspace_bytes(B, H, W, D, Dm, lv.LUVC_BF16, three, 1)
+    assert k1 < k3 and k1 >= lv.luvc_oim_workspace_bytes(B, H, W, D, lv.LUVC_BF16, three)
+    assert lv.luvc_oim_keyed_workspace_bytes(B, H, W, D, 0, lv.LUVC_BF16, three, 0) == 0
+
+
+def test_selftest_entry_points_reject_bad_arguments(L):
+    rc = L.luvc_selftest_screen_tile(None, None, 64, lv.LUVC_BF16, None, None)
+    assert rc == lv.LUVC_ERR_INVALID_ARG
+    rc = L.luvc_selftest_screen_tile(ctypes.c_void_p(256), ctypes.c_void_p(256), 12, lv.LUVC_BF16, ctypes.c_void_p(256), None)   # 24-byte rows
+    assert rc == lv.LUVC_ERR_INVALID_ARG
+    rc = L.luvc_selftest_screen_tile(ctypes.c_void_p(264), ctypes.c_void_p(256), 64, lv.LUVC_BF16, ctypes.c_void_p(256), None)   # misaligned rows
+    assert rc == lv.LUVC_ERR_INVALID_ARG
+    rc = L.luvc_selftest_screen_tile(ctypes.c_void_p(256), ctypes.c_void_p(256), 64, 9, ctypes.c_void_p(256), None)
+    assert rc == lv.LUVC_ERR_INVALID_ARG
+    rc = L.luvc_selftest_fdot2(None, None, 4, 4, None, None)
+    assert rc == lv.LUVC_ERR_INVALID_ARG
+
+
 def test_anyres_plan_and_cascade_keeps_against_the_oracle(L, oracle):
     """Host arithmetic of the library against the oracle's separately written routines, over many shapes."""
     for H in (1, 2, 7, 16, 24, 37, 64, 112, 200):
