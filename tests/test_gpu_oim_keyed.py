@@ -211,3 +211,34 @@ def test_value_enhance(oracle, dtype, shape):
     assert (np.abs(got - ref) <= ulp * np.abs(ref)).all()
     assert (got == ref).mean() > 0.999
     np.testing.assert_array_equal(got.reshape(-1, shape[-1])[0], wl.widen(v, dtype).reshape(-1, shape[-1])[0])     # s = 1: untouched
+
+
+@pytest.mark.parametrize("block", range(6))
+def test_keyed_and_wide_calls_on_seeded_random_cases(oracle, block):
+    """Seeded random grids, schedules (halving or any m), radii and key widths through luvc_oim_merge_keyed: every code path
+    behind it (fused pair kernel, one-launch wide passes, separate stages), with noisy, near-duplicate and constant keys."""
+    for seed in range(10 * block, 10 * block + 10):
+        rng = np.random.default_rng(70000 + seed)
+        dtype = "bf16" if seed % 2 else "f32"
+        radius = int(rng.choice([0, 0, 1, 1, 2, 3]))
+        B, H, W = int(rng.integers(1, 3)), int(rng.integers(1, 36)), int(rng.integers(1, 36))
+        D, Dm = int(rng.choice([8, 16, 24, 64, 136, 520])), int(rng.choice([8, 16, 40, 64, 128]))
+        halving = bool(rng.integers(0, 2))
+        passes, h, w = [], H, W
+        for _ in range(int(rng.integers(1, 5))):
+            axis = int(rng.integers(0, 2))
+            length = w if axis else h
+            if halving:
+                m = (length + 1) // 2 if length > 1 else 0
+            else:
+                m = 0 if length == 1 else min(int(rng.integers(0, (length + 1) // 2 + 1)), length - 1)
+            passes.append((axis, m))
+            if axis:
+                w -= m
+            else:
+                h -= m
+        kind = int(rng.integers(0, 3))                      # noisy keys, near-duplicate keys, constant keys (every decision a tie)
+        x = wl.cast_io(wl.smooth_field(rng, B, H, W, D, 2.0) + 0.3 * rng.standard_normal((B, H, W, D)).astype(np.float32), dtype)
+        keys = wl.smooth_field(rng, B, H, W, Dm, 2.0) * (0.0 if kind == 2 else 1.0) + 1.0 + [0.3, 1e-3, 0.0][kind] * rng.standard_normal((B, H, W, Dm)).astype(np.float32)
+        sizes = rng.integers(1, 4, (B, H, W)) if seed % 3 == 0 else None
+        run_keyed(oracle, x, wl.cast_io(keys.astype(np.float32), dtype), dtype, passes, radius, sizes=sizes, tag=f"fuzz{seed} kind{kind}")
